@@ -1,0 +1,6 @@
+"""CPU oracle for exact causal multi-head attention (forward and backward).
+
+TEST INFRASTRUCTURE ONLY.  Only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import this package.  It shares no code with
+the HIP path and the product path never calls it.
+"""
