@@ -1,0 +1,111 @@
+/* helix_attn.h -- C ABI of the MI355X (gfx950) exact attention library.
+ *
+ * The operation is the parameter-free attention part of a GPT-3 style transformer
+ * layer (paper Section 2.1 and Figure 1: the layer splits into pre-attention,
+ * attention and post-attention, and only the attention part has no parameters),
+ * computed per (batch, head) slice on [S, D] matrices:
+ *
+ *     O   = softmax(scale * Q K^T + causal mask) V          LSE_i = ln sum_j exp(scale * q_i.k_j)
+ *
+ * and its gradients dQ, dK, dV for a given dO.  Next-token prediction (Section 4.6)
+ * makes the mask causal: query i sees keys j <= i.  Dropout and biases do not exist on
+ * this path (Table 1 caption).  The backward pass works only from what the paper calls
+ * the activations "saved by flash attention" (Section 4.4, recomputation without
+ * attention): the inputs q, k, v and the outputs o, lse.  No S x S object is ever stored.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  bf16 tensors are
+ *     contiguous [B, H, S, D] (D fastest), 16-byte aligned; fp32 tensors are contiguous
+ *     [B, H, S], 4-byte aligned.  D must be 64 or 128.  B, H, S >= 1; S is arbitrary
+ *     (ragged tails are masked), B*H*S*D must stay below 2^40 elements.
+ *   - The library never allocates, frees or synchronises.  Work is enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = default stream) and the call returns as soon
+ *     as the launches are queued.
+ *   - Outputs are overwritten in full; inputs are never written; an output must not
+ *     alias any other argument.
+ *   - Arguments are validated on the host before the first HIP call.  The return value
+ *     is a helix_status; anything but HELIX_OK means nothing (or, for HELIX_ERR_LAUNCH,
+ *     only part of the work) was enqueued.
+ *   - `scale` must be finite and > 0.  `causal` != 0 applies the mask j <= i; causal == 0
+ *     runs full attention.
+ */
+#ifndef HELIX_ATTN_H
+#define HELIX_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HELIX_OK = 0,
+  HELIX_ERR_NULL_POINTER = 1,
+  HELIX_ERR_BAD_SHAPE = 2,
+  HELIX_ERR_UNSUPPORTED_HEAD_DIM = 3,
+  HELIX_ERR_MISALIGNED = 4,
+  HELIX_ERR_BAD_SCALE = 5,
+  HELIX_ERR_WORKSPACE = 6,
+  HELIX_ERR_LAUNCH = 7
+} helix_status;
+
+/* Forward (Table 1, Attention column, "Forward": two matrix products per (query, key)
+ * pair, 4*b*h*s^2 FLOPs for a full score matrix).
+ *   q, k, v : in,  bf16 [B, H, S, D]
+ *   o       : out, bf16 [B, H, S, D]
+ *   lse     : out, fp32 [B, H, S], natural-log sum-exp of the scaled scores of each row */
+int helix_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                   int B, int H, int S, int D, float scale, int causal, void* stream);
+
+/* Backward (Table 1, "Backward B": gradients wrt the inputs only; attention has no
+ * "Backward W").  Runs its kernels in order on `stream`: the row sums
+ * delta_i = sum_d dO_id * O_id, for causal attention a refinement of delta on the first
+ * HELIX_DELTA_HEAD_ROWS rows of every head (see helix_attn_bwd_delta_head), the dK/dV
+ * pass and the dQ pass.
+ *   q, k, v, o, lse : in, as given to / produced by helix_attn_fwd
+ *   dO              : in,  bf16 [B, H, S, D]
+ *   dq, dk, dv      : out, bf16 [B, H, S, D]
+ *   workspace       : device scratch of at least helix_attn_bwd_workspace_bytes(B,H,S,D)
+ *                     bytes, 256-byte aligned, owned by the caller; holds delta (fp32 [B,H,S])
+ *                     between the kernels; contents undefined afterwards. */
+int helix_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                   const void* dO, void* dq, void* dk, void* dv,
+                   void* workspace, size_t workspace_bytes,
+                   int B, int H, int S, int D, float scale, int causal, void* stream);
+
+/* Bytes of scratch helix_attn_bwd needs: B*H*S*4 rounded up to 256.  Returns 0 for an
+ * invalid shape.  Pure host arithmetic. */
+size_t helix_attn_bwd_workspace_bytes(int B, int H, int S, int D);
+
+/* The stages of helix_attn_bwd as separate calls, for per-kernel timing and profiling.
+ * Same conventions; `delta` is fp32 [B, H, S] on the device.
+ *   preprocess : delta <- rowsum(dO * O)                      (memory bound)
+ *   delta_head : delta_i <- sum_j p_ij * (dO_i . v_j) for query rows i < rows of every head,
+ *                overwriting those entries.  The two expressions are equal in exact
+ *                arithmetic; the first rows of a causal head attend to few keys, so O is
+ *                large there and its bf16 rounding would dominate the error of delta.
+ *   dkdv       : dk, dv from q, k, v, dO, lse, delta
+ *   dq         : dq     from q, k, v, dO, lse, delta */
+#define HELIX_DELTA_HEAD_ROWS 2048
+int helix_attn_bwd_preprocess(const void* o, const void* dO, float* delta,
+                              int B, int H, int S, int D, void* stream);
+int helix_attn_bwd_delta_head(const void* q, const void* k, const void* v, const void* dO,
+                              const float* lse, float* delta, int rows,
+                              int B, int H, int S, int D, float scale, int causal, void* stream);
+int helix_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* dO,
+                        const float* lse, const float* delta, void* dk, void* dv,
+                        int B, int H, int S, int D, float scale, int causal, void* stream);
+int helix_attn_bwd_dq(const void* q, const void* k, const void* v, const void* dO,
+                      const float* lse, const float* delta, void* dq,
+                      int B, int H, int S, int D, float scale, int causal, void* stream);
+
+/* Human-readable name of a helix_status value (static storage, never NULL). */
+const char* helix_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int helix_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HELIX_ATTN_H */

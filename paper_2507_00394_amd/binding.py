@@ -1,0 +1,153 @@
+"""Thin ctypes binding of ``libhelix_attn.so``: argument marshalling only.
+
+Every function has the name and argument order of its C entry point (see
+``include/helix_attn.h``); tensors are torch device tensors whose ``data_ptr()`` is
+handed over, and work is enqueued on torch's current stream.  There is no fallback: a
+missing library raises ``HelixLibraryError`` on first use.
+"""
+from __future__ import annotations
+
+import ctypes
+import pathlib
+
+import torch
+
+LIB_PATH = pathlib.Path(__file__).resolve().parent / "csrc" / "libhelix_attn.so"
+EXPORTS = ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_bwd_workspace_bytes",
+           "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head", "helix_attn_bwd_dkdv", "helix_attn_bwd_dq",
+           "helix_status_string", "helix_attn_version")
+HELIX_OK = 0
+_lib = None
+
+
+class HelixLibraryError(RuntimeError):
+    pass
+
+
+class HelixStatusError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise HelixLibraryError(f"{LIB_PATH} is not built; run `python -m paper_2507_00394_amd.build`")
+        L = ctypes.CDLL(str(LIB_PATH))
+        vp, fp, i, f, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        L.helix_attn_fwd.argtypes = [vp, vp, vp, vp, fp, i, i, i, i, f, i, vp]
+        L.helix_attn_bwd.argtypes = [vp, vp, vp, vp, fp, vp, vp, vp, vp, vp, sz, i, i, i, i, f, i, vp]
+        L.helix_attn_bwd_workspace_bytes.argtypes = [i, i, i, i]
+        L.helix_attn_bwd_workspace_bytes.restype = sz
+        L.helix_attn_bwd_preprocess.argtypes = [vp, vp, fp, i, i, i, i, vp]
+        L.helix_attn_bwd_delta_head.argtypes = [vp, vp, vp, vp, fp, fp, i, i, i, i, i, f, i, vp]
+        L.helix_attn_bwd_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, vp, vp, i, i, i, i, f, i, vp]
+        L.helix_attn_bwd_dq.argtypes = [vp, vp, vp, vp, fp, fp, vp, i, i, i, i, f, i, vp]
+        L.helix_status_string.argtypes = [i]
+        L.helix_status_string.restype = ctypes.c_char_p
+        L.helix_attn_version.argtypes = []
+        for name in ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head",
+                     "helix_attn_bwd_dkdv",
+                     "helix_attn_bwd_dq", "helix_attn_version"):
+            getattr(L, name).restype = i
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().helix_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check_bf16(name, t, shape):
+    if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: need a contiguous CUDA bfloat16 tensor of shape {tuple(shape)}")
+
+
+def _check_f32(name, t, shape):
+    if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: need a contiguous CUDA float32 tensor of shape {tuple(shape)}")
+
+
+def _raise(status, where):
+    if status != HELIX_OK:
+        raise HelixStatusError(status, where)
+
+
+def helix_attn_version() -> int:
+    return lib().helix_attn_version()
+
+
+def helix_attn_bwd_workspace_bytes(B, H, S, D) -> int:
+    return int(lib().helix_attn_bwd_workspace_bytes(B, H, S, D))
+
+
+def helix_attn_fwd(q, k, v, o, lse, scale, causal=True, stream=None):
+    """o, lse <- attention forward of q, k, v ([B,H,S,D] bf16); lse is [B,H,S] fp32."""
+    B, H, S, D = q.shape
+    for n, t in (("q", q), ("k", k), ("v", v), ("o", o)):
+        _check_bf16(n, t, (B, H, S, D))
+    _check_f32("lse", lse, (B, H, S))
+    _raise(lib().helix_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, H, S, D, float(scale), int(causal),
+                                _stream(stream)), "helix_attn_fwd")
+
+
+def helix_attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, workspace, scale, causal=True, stream=None):
+    """dq, dk, dv <- attention backward; workspace is a uint8 CUDA tensor of the required size."""
+    B, H, S, D = q.shape
+    for n, t in (("q", q), ("k", k), ("v", v), ("o", o), ("dO", dO), ("dq", dq), ("dk", dk), ("dv", dv)):
+        _check_bf16(n, t, (B, H, S, D))
+    _check_f32("lse", lse, (B, H, S))
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace: need a contiguous CUDA uint8 tensor")
+    _raise(lib().helix_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO), _ptr(dq), _ptr(dk), _ptr(dv),
+                                _ptr(workspace), workspace.numel(), B, H, S, D, float(scale), int(causal),
+                                _stream(stream)), "helix_attn_bwd")
+
+
+def helix_attn_bwd_preprocess(o, dO, delta, stream=None):
+    B, H, S, D = o.shape
+    _check_bf16("o", o, (B, H, S, D)); _check_bf16("dO", dO, (B, H, S, D)); _check_f32("delta", delta, (B, H, S))
+    _raise(lib().helix_attn_bwd_preprocess(_ptr(o), _ptr(dO), _ptr(delta), B, H, S, D, _stream(stream)),
+           "helix_attn_bwd_preprocess")
+
+
+DELTA_HEAD_ROWS = 2048
+
+
+def helix_attn_bwd_delta_head(q, k, v, dO, lse, delta, rows, scale, causal=True, stream=None):
+    B, H, S, D = q.shape
+    for n, t in (("q", q), ("k", k), ("v", v), ("dO", dO)):
+        _check_bf16(n, t, (B, H, S, D))
+    _check_f32("lse", lse, (B, H, S)); _check_f32("delta", delta, (B, H, S))
+    _raise(lib().helix_attn_bwd_delta_head(_ptr(q), _ptr(k), _ptr(v), _ptr(dO), _ptr(lse), _ptr(delta), int(rows),
+                                           B, H, S, D, float(scale), int(causal), _stream(stream)),
+           "helix_attn_bwd_delta_head")
+
+
+def helix_attn_bwd_dkdv(q, k, v, dO, lse, delta, dk, dv, scale, causal=True, stream=None):
+    B, H, S, D = q.shape
+    for n, t in (("q", q), ("k", k), ("v", v), ("dO", dO), ("dk", dk), ("dv", dv)):
+        _check_bf16(n, t, (B, H, S, D))
+    _check_f32("lse", lse, (B, H, S)); _check_f32("delta", delta, (B, H, S))
+    _raise(lib().helix_attn_bwd_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(dO), _ptr(lse), _ptr(delta), _ptr(dk), _ptr(dv),
+                                     B, H, S, D, float(scale), int(causal), _stream(stream)), "helix_attn_bwd_dkdv")
+
+
+def helix_attn_bwd_dq(q, k, v, dO, lse, delta, dq, scale, causal=True, stream=None):
+    B, H, S, D = q.shape
+    for n, t in (("q", q), ("k", k), ("v", v), ("dO", dO), ("dq", dq)):
+        _check_bf16(n, t, (B, H, S, D))
+    _check_f32("lse", lse, (B, H, S)); _check_f32("delta", delta, (B, H, S))
+    _raise(lib().helix_attn_bwd_dq(_ptr(q), _ptr(k), _ptr(v), _ptr(dO), _ptr(lse), _ptr(delta), _ptr(dq),
+                                   B, H, S, D, float(scale), int(causal), _stream(stream)), "helix_attn_bwd_dq")

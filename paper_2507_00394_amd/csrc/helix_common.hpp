@@ -1,0 +1,137 @@
+// Device-side building blocks shared by the gfx950 attention kernels: vector types,
+// the 32x32x16 bf16 MFMA, LDS tile staging with a bank-conflict-free swizzle, the
+// transposing LDS read and the cross-half lane exchange.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace helix {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define HELIX_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// D(32x32, fp32) += A(32x16, bf16) * B(16x32, bf16).  Lane l supplies A[l%32][8*(l/32)..+7]
+// and B[8*(l/32)..+7][l%32]; accumulator register v of lane l is
+// D[8*(v/4) + 4*(l/32) + v%4][l%32].
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Value held by the lane 32 positions away combined with this lane's: both halves of the
+// wave end up with the same result.
+__device__ __forceinline__ float half_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// LDS tiles are [rows][D] bf16 with the 16-byte chunks of each row permuted by an XOR
+// that depends on the row, so that both access patterns below hit all 64 banks:
+//   - ds_read_b128 by 16 lanes on 16 consecutive rows at the same logical chunk,
+//   - ds_read_b64_tr_b16 by 32 lanes on 4 consecutive rows x 64 contiguous bytes.
+template <int D>
+__device__ __forceinline__ int swizzle(int row) {
+  if constexpr (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+  else return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+}
+template <int D>
+__device__ __forceinline__ int lds_chunk_off(int row, int chunk) {
+  return row * (D * 2) + ((chunk ^ swizzle<D>(row)) << 4);
+}
+
+// One 16-byte chunk from global memory, zero when the row is past the end.
+__device__ __forceinline__ u32x4 load_chunk(const __bf16* base, int row, int nrows, int row_stride, int col) {
+  u32x4 z = {0u, 0u, 0u, 0u};
+  if (row < nrows) z = *reinterpret_cast<const u32x4*>(base + (size_t)row * row_stride + col);
+  return z;
+}
+
+// Register-staged copy of a [ROWS][D] bf16 tile: `fetch` issues the global loads, `commit`
+// writes them to LDS (swizzled).  NT threads cooperate; chunk id = tid + NT*i.
+template <int D, int ROWS, int NT>
+struct TileStage {
+  static constexpr int CH = D / 8;                 // 16-byte chunks per row
+  static constexpr int N = (ROWS * CH + NT - 1) / NT;
+  u32x4 r[N];
+  __device__ __forceinline__ void fetch(const __bf16* head_base, int row0, int nrows, int tid) {
+#pragma unroll
+    for (int i = 0; i < N; i++) {
+      int id = tid + NT * i;
+      int row = id / CH, c = id % CH;
+      if (ROWS * CH % NT == 0 || id < ROWS * CH) r[i] = load_chunk(head_base, row0 + row, nrows, D, c * 8);
+    }
+  }
+  __device__ __forceinline__ void commit(char* lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < N; i++) {
+      int id = tid + NT * i;
+      int row = id / CH, c = id % CH;
+      if (ROWS * CH % NT == 0 || id < ROWS * CH) *reinterpret_cast<u32x4*>(lds + lds_chunk_off<D>(row, c)) = r[i];
+    }
+  }
+};
+
+// MFMA operand whose 8 contraction slots are contiguous in memory: row `row`, elements
+// 16*ks + 8*half .. +7 of a swizzled LDS tile.
+template <int D>
+__device__ __forceinline__ bf16x8 lds_operand(const char* tile, int row, int ks, int half) {
+  return *reinterpret_cast<const bf16x8*>(tile + lds_chunk_off<D>(row, 2 * ks + half));
+}
+
+// MFMA operand whose contraction index runs over tile ROWS (the tile is stored row-major
+// with the lane's own index along the row): lane l gets, for column col0 + l%32, the rows
+//   row0 + 4*(l/32) + {0,1,2,3}   and   row0 + 8 + 4*(l/32) + {0,1,2,3},
+// which is exactly the slot order of a bf16 pack of accumulator registers 8t..8t+7.
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane i supplies the address of row
+// i/4, columns 4*(i%4)..+3 and receives column i of those four rows.
+template <int D>
+__device__ __forceinline__ bf16x8 lds_operand_tr(const char* tile, int row0, int col0, int lane) {
+  int i = lane & 15;
+  int col = col0 + ((lane >> 4) & 1) * 16 + (i & 3) * 4;
+  int r0 = row0 + (lane >> 5) * 4 + (i >> 2);
+  int off0 = lds_chunk_off<D>(r0, col >> 3) + (col & 7) * 2;
+  int off1 = lds_chunk_off<D>(r0 + 8, col >> 3) + (col & 7) * 2;
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HELIX_LDS(s16x4, tile + off0));
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HELIX_LDS(s16x4, tile + off1));
+  s16x8 ab = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, ab);
+}
+
+// bf16 pack (round to nearest even) of accumulator registers 8t..8t+7.
+__device__ __forceinline__ bf16x8 pack_half(const f32x16& acc, int t) {
+  f32x8 x;
+#pragma unroll
+  for (int e = 0; e < 8; e++) x[e] = acc[8 * t + e];
+  return __builtin_convertvector(x, bf16x8);
+}
+
+// Map a linear workgroup id to (batch*head slice, tile) so that the 8 XCDs (workgroup id
+// mod 8 selects the XCD) each sweep whole heads, heaviest tiles first; `heavy_last` tiles
+// are those with the highest index (forward, dQ) or the lowest (dK/dV).
+struct TileCoord { int bh; int tile; bool valid; };
+__device__ __forceinline__ TileCoord map_block(int n, int BH, int T, bool heavy_is_high) {
+  TileCoord c;
+  int xcd = n & 7, s = n >> 3;
+  c.bh = xcd + 8 * (s / T);
+  int t = s % T;
+  c.tile = heavy_is_high ? (T - 1 - t) : t;
+  c.valid = c.bh < BH;
+  return c;
+}
+
+}  // namespace helix

@@ -119,12 +119,13 @@ def sample_rows(cfg: AttnConfig, n: int = 256, seed: int = 7):
     return picks[:n]
 
 
-def sample_cols(cfg: AttnConfig, n_full: int = 64, n_tail: int = 128, tail: int = 4096, seed: int = 11):
+def sample_cols(cfg: AttnConfig, n_full: int = 64, n_tail: int = 128, tail: int = 1024, tail_heads: int = 16, seed: int = 11):
     """Key-column sample: ``full`` = {bh: [j...]} over the whole range for the first and last
-    head, ``tail`` = [(bh, j)] with j in the last ``tail`` positions of random heads."""
+    head (tile edges forced), ``tail`` = {bh: [j...]} with j in the last ``tail`` positions of
+    up to ``tail_heads`` randomly drawn heads (``n_tail`` draws in total)."""
     S, BH = cfg.S, cfg.B * cfg.H
     rng = np.random.Generator(np.random.Philox(key=np.array([SEED, (seed << 32) | cfg.cfg_id], dtype=np.uint64)))
-    forced = sorted({j for j in [0, 1, 127, 128, S // 2, S - 128, S - 1] if 0 <= j < S})
+    forced = sorted({j for j in [0, 1, 127, 128, 255, 256, S // 2, S - 128, S - 1] if 0 <= j < S})
     full = {}
     for bh in sorted({0, BH - 1}):
         cols = list(forced)
@@ -132,5 +133,8 @@ def sample_cols(cfg: AttnConfig, n_full: int = 64, n_tail: int = 128, tail: int 
             cols.append(int(rng.integers(S)))
         full[bh] = sorted(set(cols))
     lo = max(0, S - tail)
-    tail_cols = [(int(rng.integers(BH)), int(rng.integers(lo, S))) for _ in range(n_tail)]
-    return full, tail_cols
+    heads = sorted({int(rng.integers(BH)) for _ in range(tail_heads)})
+    tail_cols = {bh: set() for bh in heads}
+    for _ in range(n_tail):
+        tail_cols[heads[int(rng.integers(len(heads)))]].add(int(rng.integers(lo, S)))
+    return full, {bh: sorted(c) for bh, c in tail_cols.items() if c}

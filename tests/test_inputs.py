@@ -45,5 +45,5 @@ def test_samples_are_stratified_and_in_range():
         full, tail = I.sample_cols(cfg)
         assert set(full) == {0, cfg.B * cfg.H - 1}
         assert all({0, 1, 127, 128, cfg.S - 1} <= set(c) for c in full.values())
-        assert len(tail) == 128 and all(cfg.S - 4096 <= j < cfg.S for _, j in tail)
+        assert 100 <= sum(len(c) for c in tail.values()) <= 128 and all(cfg.S - 1024 <= j < cfg.S for c in tail.values() for j in c)
         assert rows == I.sample_rows(cfg)
