@@ -1,0 +1,143 @@
+"""Benchmark of the causal attention forward + backward hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch: forward, delta
+preprocess, delta refinement of the first rows, dK/dV pass and dQ pass, all through the
+C-ABI library on torch's current stream, with inputs resident in HBM.  The default
+workload is the 7B layer at 128k tokens (B=1, H=32, S=131072, D=128).
+
+Prints ONE JSON line.  ``value`` counts 14*D FLOPs per unmasked (query, key) pair per head
+(forward 4*D, backward 10*D including the score recomputation); the paper's Table 1
+convention (12*D, no recomputation) is reported beside it.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+PEAK_FLOP_PER_CLK_PER_CU = 4096          # dense bf16 MFMA, 4 SIMDs x 1024
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload id 1..5 (default 4: the metric's workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=12288)
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, sample_tokens):
+    """The oracle as it stands, timed on the host cores on a bounded sample."""
+    from oracle import attention_ref as A
+    from paper_2507_00394_amd import inputs as I
+
+    S = min(cfg.S, sample_tokens)
+    x = I.head_inputs(cfg, 0, S=S)
+    t0 = time.perf_counter()
+    A.head_backward(x["q"], x["k"], x["v"], x["dO"], cfg.scale, cfg.causal)
+    dt = time.perf_counter() - t0
+    flops = 14 * cfg.D * (S * (S + 1) // 2 if cfg.causal else S * S)
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle.attention_ref.head_backward (fp64 forward + gradients) on the first {S} tokens of head 0 "
+                      f"of the workload, {dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (every (batch, head) slice is independent; "
+              "sharding over heads needs no collective and is not part of this run); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2507_00394_amd import binding as hx
+    from paper_2507_00394_amd import inputs as I
+
+    cfg = I.CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    n_cu, clock_khz = hx.helix_attn_device_info()
+    clock_ghz = clock_khz / 1e6
+    peak_tflops = n_cu * PEAK_FLOP_PER_CLK_PER_CU * clock_ghz / 1e3
+
+    bits = I.all_inputs_bits(cfg, threads=16)
+    q, k, v, g = (torch.from_numpy(bits[t].view(np.int16)).to(dev).view(torch.bfloat16) for t in ("q", "k", "v", "dO"))
+    del bits
+    B, H, S, D = q.shape
+    o = torch.empty_like(q); lse = torch.empty((B, H, S), dtype=torch.float32, device=dev)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    delta = torch.empty_like(lse)
+    stages = ["fwd", "preprocess", "delta_head", "dkdv", "dq"]
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0); hx.helix_attn_fwd(q, k, v, o, lse, cfg.scale, cfg.causal)
+        mark(1); hx.helix_attn_bwd_preprocess(o, g, delta)
+        mark(2)
+        if cfg.causal:
+            hx.helix_attn_bwd_delta_head(q, k, v, g, lse, delta, hx.DELTA_HEAD_ROWS, cfg.scale, True)
+        mark(3); hx.helix_attn_bwd_dkdv(q, k, v, g, lse, delta, dk, dv, cfg.scale, cfg.causal)
+        mark(4); hx.helix_attn_bwd_dq(q, k, v, g, lse, delta, dq, cfg.scale, cfg.causal)
+        mark(5)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms = {n: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)])) for i, n in enumerate(stages)}
+    pairs = cfg.pairs_per_head * B * H
+    unit = pairs * D
+    ms_step = wall * 1e3 / args.steps
+    value = 14 * unit / (wall / args.steps) / 1e12
+    ms_bwd = ms["preprocess"] + ms["delta_head"] + ms["dkdv"] + ms["dq"]
+    # dominant kernel: the dK/dV pass (4 contractions = 8*D FLOPs per unmasked pair)
+    dom = max(("fwd", 4), ("dkdv", 8), ("dq", 6), key=lambda kv: ms[kv[0]])
+    dom_tflops = dom[1] * unit / (ms[dom[0]] * 1e-3) / 1e12
+    pre_bytes = 2 * q.numel() * 2 + lse.numel() * 4
+    out = {
+        "metric": "causal attn fwd+bwd TFLOP/s @H=32,D=128,S=128k; % of bf16 MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config {cfg.cfg_id}: causal MHA fwd+bwd, B={B} H={H} S={S} D={D}, bf16 iid N(0,1)"
+                               + (f", K x{cfg.k_mult:g}" if cfg.k_mult != 1 else "") + f", scale=1/sqrt({D})",
+                   "B": B, "H": H, "S": S, "D": D, "flops_per_pair": "14*D (fwd 4*D + bwd 10*D)"},
+        "pct_of_bf16_mfma_peak": 100 * value / peak_tflops,
+        "peak_tflops_denominator": peak_tflops,
+        "peak_denominator": f"{n_cu} CU x {PEAK_FLOP_PER_CLK_PER_CU} flop/clk x {clock_ghz:.2f} GHz",
+        "fwd_tflops": 4 * unit / (ms["fwd"] * 1e-3) / 1e12,
+        "bwd_tflops": 10 * unit / (ms_bwd * 1e-3) / 1e12,
+        "fwd_bwd_tflops_table1_convention": 12 * unit / (wall / args.steps) / 1e12,
+        "kernel_ms": ms,
+        "preprocess_gbs": pre_bytes / (ms["preprocess"] * 1e-3) / 1e9,
+        "preprocess_frac_of_hbm_peak": pre_bytes / (ms["preprocess"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "mfma", "kernel": dom[0], "achieved": dom_tflops, "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": dom_tflops / 2500.0, "traffic": None,
+                     "flops_per_launch": dom[1] * unit, "avg_launch_ms": ms[dom[0]]},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

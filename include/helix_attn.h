@@ -99,6 +99,10 @@ int helix_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d
                       const float* lse, const float* delta, void* dq,
                       int B, int H, int S, int D, float scale, int causal, void* stream);
 
+/* Compute-unit count and peak engine clock (kHz) of the current HIP device, the two
+ * factors of the MFMA roofline (CUs x 4096 bf16 FLOP/clk x clock).  Host pointers. */
+int helix_attn_device_info(int* compute_units, int* clock_khz);
+
 /* Human-readable name of a helix_status value (static storage, never NULL). */
 const char* helix_status_string(int status);
 

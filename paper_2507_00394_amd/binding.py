@@ -15,7 +15,7 @@ import torch
 LIB_PATH = pathlib.Path(__file__).resolve().parent / "csrc" / "libhelix_attn.so"
 EXPORTS = ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_bwd_workspace_bytes",
            "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head", "helix_attn_bwd_dkdv", "helix_attn_bwd_dq",
-           "helix_status_string", "helix_attn_version")
+           "helix_attn_device_info", "helix_status_string", "helix_attn_version")
 HELIX_OK = 0
 _lib = None
 
@@ -48,6 +48,8 @@ def lib() -> ctypes.CDLL:
         L.helix_status_string.argtypes = [i]
         L.helix_status_string.restype = ctypes.c_char_p
         L.helix_attn_version.argtypes = []
+        L.helix_attn_device_info.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+        L.helix_attn_device_info.restype = i
         for name in ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head",
                      "helix_attn_bwd_dkdv",
                      "helix_attn_bwd_dq", "helix_attn_version"):
@@ -86,6 +88,13 @@ def _raise(status, where):
 
 def helix_attn_version() -> int:
     return lib().helix_attn_version()
+
+
+def helix_attn_device_info():
+    """(compute units, peak engine clock in kHz) of the current device."""
+    cu, khz = ctypes.c_int(0), ctypes.c_int(0)
+    _raise(lib().helix_attn_device_info(ctypes.byref(cu), ctypes.byref(khz)), "helix_attn_device_info")
+    return cu.value, khz.value
 
 
 def helix_attn_bwd_workspace_bytes(B, H, S, D) -> int:

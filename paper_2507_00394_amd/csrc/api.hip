@@ -124,6 +124,16 @@ int helix_attn_bwd(const void* q, const void* k, const void* v, const void* o, c
   return launched(helix::launch_bwd_dq(q, k, v, dO, lse, delta, dq, BH, S, D, scale, causal != 0, st));
 }
 
+int helix_attn_device_info(int* compute_units, int* clock_khz) {
+  if (!compute_units || !clock_khz) return HELIX_ERR_NULL_POINTER;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return HELIX_ERR_LAUNCH;
+  *compute_units = prop.multiProcessorCount;
+  *clock_khz = prop.clockRate;
+  return HELIX_OK;
+}
+
 const char* helix_status_string(int status) {
   switch (status) {
     case HELIX_OK: return "ok";

@@ -1,0 +1,78 @@
+"""C-ABI library on the host (no GPU): it loads, exports every symbol the header declares,
+and rejects bad arguments before touching HIP."""
+import ctypes
+import pathlib
+import re
+
+import pytest
+
+from paper_2507_00394_amd import binding as hx
+
+ROOT = pathlib.Path(__file__).resolve().parents[1]
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not hx.LIB_PATH.exists():
+        from paper_2507_00394_amd import build
+
+        build.build()
+    return hx.lib()
+
+
+def declared_functions():
+    text = (ROOT / "include" / "helix_attn.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(helix_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert set(names) == set(hx.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_status_strings(L):
+    assert L.helix_attn_version() >= 100
+    seen = {hx.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and hx.status_string(0) == "ok" and hx.status_string(99) == "unknown status"
+
+
+def test_workspace_bytes(L):
+    assert hx.helix_attn_bwd_workspace_bytes(1, 2, 512, 64) == 4096
+    assert hx.helix_attn_bwd_workspace_bytes(1, 1, 1, 64) == 256
+    assert hx.helix_attn_bwd_workspace_bytes(1, 32, 131072, 128) == 32 * 131072 * 4
+    assert hx.helix_attn_bwd_workspace_bytes(1, 1, 10, 96) == 0
+    assert hx.helix_attn_bwd_workspace_bytes(0, 1, 10, 64) == 0
+
+
+def test_validation_precedes_any_device_work(L):
+    """Fake but aligned addresses: every call must fail in validation, never reach a launch."""
+    p = ctypes.c_void_p(0x10000)
+    odd = ctypes.c_void_p(0x10008)
+    fwd = lambda **kw: L.helix_attn_fwd(kw.get("q", p), p, p, kw.get("o", p), kw.get("lse", p), kw.get("B", 1), kw.get("H", 1),
+                                         kw.get("S", 8), kw.get("D", 64), kw.get("scale", 0.1), 1, None)
+    assert fwd(q=None) == 1 and fwd(o=None) == 1 and fwd(lse=None) == 1
+    assert fwd(B=0) == 2 and fwd(S=0) == 2 and fwd(H=-3) == 2 and fwd(S=(1 << 24) + 1) == 2
+    assert fwd(D=96) == 3 and fwd(D=256) == 3
+    assert fwd(q=odd) == 4 and fwd(lse=ctypes.c_void_p(0x10002)) == 4
+    assert fwd(scale=0.0) == 5 and fwd(scale=-1.0) == 5 and fwd(scale=float("nan")) == 5 and fwd(scale=float("inf")) == 5
+    bwd = lambda ws=p, wsb=1 << 20, **kw: L.helix_attn_bwd(p, p, p, p, p, kw.get("dO", p), p, p, kw.get("dv", p), ws, wsb, 1, 2, 512,
+                                                          kw.get("D", 64), kw.get("scale", 0.1), 1, None)
+    assert bwd(dO=None) == 1 and bwd(dv=None) == 1 and bwd(ws=None) == 1
+    assert bwd(ws=ctypes.c_void_p(0x10010)) == 4
+    assert bwd(wsb=4095) == 6
+    assert bwd(D=32) == 3 and bwd(scale=0.0) == 5
+    assert L.helix_attn_bwd_preprocess(p, None, p, 1, 1, 8, 64, None) == 1
+    assert L.helix_attn_bwd_delta_head(p, p, p, p, p, p, -1, 1, 1, 8, 64, 0.1, 1, None) == 2
+    assert L.helix_attn_bwd_dkdv(p, p, p, p, p, p, p, odd, 1, 1, 8, 64, 0.1, 1, None) == 4
+    assert L.helix_attn_bwd_dq(p, p, p, p, p, p, p, 1, 1, 8, 128, -0.1, 1, None) == 5
+
+
+def test_binding_refuses_cpu_tensors(L):
+    import torch
+
+    x = torch.zeros(1, 1, 8, 64, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        hx.helix_attn_fwd(x, x, x, x, torch.zeros(1, 1, 8), 0.1)
