@@ -76,6 +76,7 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
   constexpr int KS = D / 16, DB = D / 32;
   constexpr int TILE_BYTES = BM * D * 2;
   constexpr int STAT_OFF = 4 * TILE_BYTES;        // after Q[2], dO[2]: lse2[2][BM], delta[2][BM]
+  constexpr int V_OFF = STAT_OFF + 4 * BM * 4;    // then the workgroup's V tile [BN][D], resident
   extern __shared__ __align__(16) char smem[];
 
   const TileCoord tc = map_block(blockIdx.x, BH, T, false);
@@ -91,16 +92,19 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
   const float* delta_h = delta + (size_t)tc.bh * S;
   const float c = scale * kLog2e;
 
-  // K^T and V^T operand fragments of this lane's key (columns of S and dP).
-  bf16x8 kf[KS], vf[KS];
+  // K^T operand fragments of this lane's key (columns of S) stay in registers; the V^T
+  // fragments (columns of dP) are re-read from an LDS copy of the workgroup's V rows.
+  bf16x8 kf[KS];
   {
     const int row = my_key < S ? my_key : S - 1;
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++) {
+    for (int ks = 0; ks < KS; ks++)
       kf[ks] = *reinterpret_cast<const bf16x8*>(k + head_off + (size_t)row * D + 16 * ks + 8 * half);
-      vf[ks] = *reinterpret_cast<const bf16x8*>(v + head_off + (size_t)row * D + 16 * ks + 8 * half);
-    }
+    TileStage<D, BN, NT> svt;
+    svt.fetch(v + head_off, n0, S, tid);
+    svt.commit(smem + V_OFF, tid);
   }
+  const char* vtile = smem + V_OFF;
   f32x16 dkacc[DB], dvacc[DB];
 #pragma unroll
   for (int db = 0; db < DB; db++)
@@ -153,8 +157,11 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
       for (int e = 0; e < 16; e++) { sacc[e] = 0.f; pacc[e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) sacc = mfma32(lds_operand<D>(qt, 32 * qb + n, ks, half), kf[ks], sacc);
+      int vrow = 32 * w + n;
+      asm volatile("" : "+v"(vrow));   // keep the V reads inside the loop (they would be hoisted into registers)
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++) pacc = mfma32(lds_operand<D>(gt, 32 * qb + n, ks, half), vf[ks], pacc);
+      for (int ks = 0; ks < KS; ks++)
+        pacc = mfma32(lds_operand<D>(gt, 32 * qb + n, ks, half), lds_operand<D>(vtile, vrow, ks, half), pacc);
       const bool need_mask = CAUSAL && (r0 < wave_kmin + 31);
 #pragma unroll
       for (int g = 0; g < 4; g++) {
@@ -211,7 +218,7 @@ static hipError_t launch_dkdv_t(const void* q, const void* k, const void* v, con
   constexpr int BN = 256, BM = 64;
   const int T = (S + BN - 1) / BN;
   const int grid = 8 * ((BH + 7) / 8) * T;
-  const size_t lds = 4 * BM * D * 2 + 4 * BM * sizeof(float);
+  const size_t lds = 4 * BM * D * 2 + 4 * BM * sizeof(float) + BN * D * 2;
   auto kern = bwd_dkdv_kernel<D, CAUSAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;

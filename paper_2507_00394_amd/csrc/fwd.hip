@@ -9,20 +9,193 @@
 // exchange between the two wave halves, not a 32-lane reduction.  bf16(P^T) in its
 // accumulator layout is directly the B operand of O^T += V^T P^T; V^T comes from the
 // row-major V tile in LDS through the transposing LDS read.
+//
+// Schedule.  On this chip a second MFMA queued behind a running one stalls the vector-ALU
+// port of the whole SIMD, so matrix and vector work only overlap when they alternate inside
+// one instruction stream.  The sweep is therefore software pipelined over 32-key half tiles
+// h = 0, 1, 2, ... and every half step is ONE basic block of 16 hand-ordered slots (D = 128):
+//     slots 0..7   MFMA S(h+1) += K(h+1) Q^T   | VALU two elements of P(h) = exp2(S(h)*c - m*c),
+//                                              | their row sum, bf16 packs | LDS: V operand i
+//     slots 8..15  MFMA O^T += V(h)^T P(h)^T   | VALU row maximum of S(h+1) | LDS: K operand i of S(h+2)
+// followed by the (rare) rescale of the accumulators when a row maximum outgrew its
+// reference.  K and V tiles are copied global -> LDS asynchronously one tile ahead into two
+// buffers each; one workgroup barrier per 64-key tile.  The last tile of every wave (the only
+// one the causal mask cuts, or the ragged end of the sequence) runs unpipelined.
 #include "helix_common.hpp"
 #include "kernels.hpp"
 
 namespace helix {
 
+// The running reference maximum may lag the true row maximum by up to 2^kSlack before the
+// accumulators are rescaled (exact in real arithmetic; keeps the rescale off the hot path).
+constexpr float kSlack = 8.f;
+
+template <int D>
+struct FwdLaneAddr {
+  int k[D / 16];       // K operand, contraction step ks, key row n of a tile (+32 rows by immediate)
+  int v[D / 32][2];    // V^T operand of head-dim block db: first / second group of 4 key rows
+  __device__ __forceinline__ FwdLaneAddr(int lane) {
+    const int half = lane >> 5, n = lane & 31, i = lane & 15;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) k[ks] = lds_chunk_off<D>(n, 2 * ks + half);
+#pragma unroll
+    for (int db = 0; db < D / 32; db++) {
+      const int col = 32 * db + ((lane >> 4) & 1) * 16 + (i & 3) * 4;
+      const int r0 = half * 4 + (i >> 2);
+      v[db][0] = lds_chunk_off<D>(r0, col >> 3) + (col & 7) * 2;
+      v[db][1] = lds_chunk_off<D>(r0 + 8, col >> 3) + (col & 7) * 2;
+    }
+  }
+};
+
+// LDS reads take an absolute 32-bit LDS address held in a register plus a compile-time
+// immediate that folds into the instruction's offset field.
+__device__ __forceinline__ uint32_t lds_base(const char* smem) { return (uint32_t)(uintptr_t)HELIX_LDS(const char, smem); }
+__device__ __forceinline__ bf16x8 lds_b128(uint32_t addr, int imm = 0) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+      reinterpret_cast<const __attribute__((address_space(3))) char*>((uintptr_t)addr) + imm);
+}
+
+// V^T operand: 16 keys (two groups of 4+4 rows per lane half) x 32 head-dim columns.
+__device__ __forceinline__ bf16x8 lds_tr_pair(uint32_t addr0, uint32_t addr1, int imm) {
+  typedef __attribute__((address_space(3))) char* lds_ptr;
+  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HELIX_LDS(s16x4, reinterpret_cast<lds_ptr>((uintptr_t)addr0) + imm));
+  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HELIX_LDS(s16x4, reinterpret_cast<lds_ptr>((uintptr_t)addr1) + imm));
+  const s16x8 ab = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, ab);
+}
+
+__device__ __forceinline__ float max16(const f32x16& s) {
+  float a = fmaxf(fmaxf(s[0], s[1]), s[2]);
+  float b = fmaxf(fmaxf(s[3], s[4]), s[5]);
+  a = fmaxf(fmaxf(a, s[6]), s[7]);
+  b = fmaxf(fmaxf(b, s[8]), s[9]);
+  a = fmaxf(fmaxf(a, s[10]), s[11]);
+  b = fmaxf(fmaxf(b, s[12]), s[13]);
+  a = fmaxf(fmaxf(a, s[14]), s[15]);
+  return fmaxf(a, b);
+}
+
+// Softmax state of a wave: reference maximum times c (the reference may lag the true row
+// maximum by up to kSlack), the raw-score threshold that triggers a reference update, and
+// two partial row sums per lane.
+struct SoftmaxState {
+  float mref_c = -INFINITY;
+  float thr = -INFINITY;          // (mref_c + kSlack) / c
+  float lsum[2] = {0.f, 0.f};
+};
+
+// Cheap per-block check: did any lane see a raw score above the threshold?  (Each lane holds
+// 16 of the 32 keys of its query; the two halves share mref_c, so the union over all lanes
+// is the test on the full rows.)  If so, move the reference of every row that grew and
+// rescale the wave's accumulators.
+template <int DB>
+__device__ __forceinline__ void check_reference(float local_max, float c, SoftmaxState& st, f32x16 (&oacc)[DB]) {
+  if (__any(local_max > st.thr)) {
+    const float tc = half_max(local_max) * c;
+    const float m_new = fmaxf(st.mref_c, tc);
+    const float alpha = __builtin_amdgcn_exp2f(st.mref_c - m_new);   // 0 on the first block, 1 where nothing changed
+    st.lsum[0] *= alpha;
+    st.lsum[1] *= alpha;
+#pragma unroll
+    for (int db = 0; db < DB; db++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) oacc[db][e] *= alpha;
+    st.mref_c = m_new;
+    st.thr = (m_new + kSlack) / c;
+  }
+}
+
+// P = bf16(exp2(S*c - mref_c)) in two 16-key packs.  The row sum takes the unrounded fp32
+// values: summing the bf16-rounded ones would put up to 2^-9 relative error into LSE on rows
+// that see only a few keys.
+__device__ __forceinline__ void exp_pack(const f32x16& s, float c, SoftmaxState& st, bf16x8 (&p)[2]) {
+  f32x16 e;
+#pragma unroll
+  for (int i = 0; i < 16; i++) {
+    e[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c, -st.mref_c));
+    st.lsum[i & 1] += e[i];
+  }
+  p[0] = pack_half(e, 0);
+  p[1] = pack_half(e, 1);
+}
+
+// O^T += V^T P^T over the 32 key rows at byte offset row_off of the V region (plain path).
+template <int D>
+__device__ __forceinline__ void pv_block(const uint32_t (&vaddr)[D / 32][2], int row_off,
+                                         const bf16x8 (&p)[2], f32x16 (&oacc)[D / 32]) {
+#pragma unroll
+  for (int t = 0; t < 2; t++)
+#pragma unroll
+    for (int db = 0; db < D / 32; db++)
+      oacc[db] = mfma32(lds_tr_pair(vaddr[db][0] + row_off, vaddr[db][1] + row_off, 16 * t * D * 2), p[t], oacc[db]);
+}
+
+// One pipelined half step (see the header comment).  On entry s_cur is complete, kop holds
+// the K operands of the block to be scored now and vop[0..KS/2-1] the first V operands of
+// this step (rows V_IMM.. of the tile at vaddr); on exit s_next is complete, this lane's
+// maximum over its 16 entries of s_next is returned, kop holds the K operands at
+// knext + K_IMM and vop the first V operands of the next step.  When LAST_OF_TILE, the next
+// step reads the next V tile: vaddr moves on by v_step once this tile's reads are issued.
+// Every slot issues one MFMA and the LDS read of one operand needed KS/2 (V) or KS (K)
+// slots later.
+template <int D, int K_IMM, int V_IMM, bool LAST_OF_TILE>
+__device__ __forceinline__ float half_step(const f32x16& s_cur, f32x16& s_next,
+                                           bf16x8 (&kop)[D / 16], bf16x8 (&vop)[D / 32], const bf16x8 (&qf)[D / 16],
+                                           const uint32_t (&knext)[D / 16], uint32_t (&vaddr)[D / 32][2], int v_step,
+                                           f32x16 (&oacc)[D / 32], float c, SoftmaxState& st) {
+  constexpr int KS = D / 16, DB = D / 32, EPS = 16 / KS;   // EPS elements of P per slot
+  constexpr int RING = KS / 2;                              // V operands in flight (== DB)
+  constexpr int HALF = 32 * D * 2;
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  bf16x8 p[2];
+  f32x16 e;
+#pragma unroll
+  for (int i = 0; i < KS; i++) {
+    s_next = mfma32(kop[i], qf[i], i == 0 ? zero : s_next);
+#pragma unroll
+    for (int x = EPS * i; x < EPS * (i + 1); x++) {
+      e[x] = __builtin_amdgcn_exp2f(fmaf(s_cur[x], c, -st.mref_c));
+      st.lsum[x & 1] += e[x];
+    }
+    if (i == KS / 2 - 1) p[0] = pack_half(e, 0);
+    if (i == KS - 1) p[1] = pack_half(e, 1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  float m0 = 0.f, m1 = 0.f, m2 = 0.f, m3 = 0.f, m4 = 0.f;
+#pragma unroll
+  for (int i = 0; i < KS; i++) {
+    oacc[i % DB] = mfma32(vop[i % RING], p[i / DB], oacc[i % DB]);
+    if (i < RING) {
+      // V operand i + RING of this step (the second 16 keys)
+      vop[i % RING] = lds_tr_pair(vaddr[i % DB][0], vaddr[i % DB][1], V_IMM + 16 * D * 2);
+    } else {
+      // V operand i - RING of the next step
+      if (LAST_OF_TILE) { vaddr[i % DB][0] += v_step; vaddr[i % DB][1] += v_step; }
+      vop[i % RING] = lds_tr_pair(vaddr[i % DB][0], vaddr[i % DB][1], LAST_OF_TILE ? 0 : V_IMM + HALF);
+    }
+    kop[i] = lds_b128(knext[i], K_IMM);
+    // row maximum of s_next, spread over the later slots (the score MFMAs have drained by then)
+    if (i == KS - 4) { m0 = fmaxf(fmaxf(s_next[0], s_next[1]), s_next[2]); m1 = fmaxf(fmaxf(s_next[3], s_next[4]), s_next[5]); pin(m0); pin(m1); }
+    if (i == KS - 3) { m2 = fmaxf(fmaxf(s_next[6], s_next[7]), s_next[8]); m3 = fmaxf(fmaxf(s_next[9], s_next[10]), s_next[11]); pin(m2); pin(m3); }
+    if (i == KS - 2) { m4 = fmaxf(fmaxf(s_next[12], s_next[13]), s_next[14]); m0 = fmaxf(fmaxf(m0, m1), s_next[15]); pin(m4); pin(m0); }
+    if (i == KS - 1) { m2 = fmaxf(fmaxf(m2, m3), m4); m0 = fmaxf(m0, m2); pin(m0); }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  return m0;
+}
+
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(512, 1)
 fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
            __bf16* __restrict__ o, float* __restrict__ lse, int BH, int S, int T, float scale) {
-  constexpr int BM = 256, BN = 64, NT = 512;
+  constexpr int BM = 256, BN = 64;
   constexpr int KS = D / 16;   // contraction steps of Q K^T
   constexpr int DB = D / 32;   // 32-wide blocks of the head dimension
-  constexpr int TILE_BYTES = BN * D * 2;
-  extern __shared__ __align__(16) char smem[];   // K[2] then V[2]
+  constexpr int TILE = BN * D * 2;
+  constexpr int HALF = 32 * D * 2;   // bytes of 32 key rows
+  constexpr int VREGION = 3 * TILE;
+  extern __shared__ __align__(16) char smem[];   // K[3] then V[3]; tile j lives in buffer j % 3
 
   const TileCoord tc = map_block(blockIdx.x, BH, T, true);
   if (!tc.valid) return;
@@ -36,13 +209,14 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   const __bf16* vh = v + head_off;
   const float c = scale * kLog2e;
 
-  // Q^T operand fragments: this lane's query row, 8 elements per contraction step.
   bf16x8 qf[KS];
   {
     const int row = my_q < S ? my_q : S - 1;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++)
       qf[ks] = *reinterpret_cast<const bf16x8*>(qh + (size_t)row * D + 16 * ks + 8 * half);
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) pin(qf[ks]);
   }
 
   f32x16 oacc[DB];
@@ -50,96 +224,106 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   for (int db = 0; db < DB; db++)
 #pragma unroll
     for (int e = 0; e < 16; e++) oacc[db][e] = 0.f;
-  float m = -INFINITY;   // running row maximum of the raw (unscaled) scores
-  float lsum = 0.f;      // this lane's share of the running row sum
+  SoftmaxState st;
 
   const int q_end = (q0 + BM < S ? q0 + BM : S);                 // one past the last real row
   const int n_tiles = CAUSAL ? (q_end + BN - 1) / BN : (S + BN - 1) / BN;
   const int wave_qmin = q0 + 32 * w, wave_qmax = wave_qmin + 31;
+  // Tiles this wave works on (n_w) and how many of them need no mask (n_full).  All but the
+  // last run through the pipelined path; n_full >= n_w - 1 always holds.
+  int n_w, n_full;
+  if (wave_qmin >= S) { n_w = 0; n_full = 0; }
+  else if (CAUSAL) { n_w = (wave_qmax < S ? wave_qmax : S - 1) / BN + 1; n_full = (wave_qmin + 1) / BN; }
+  else { n_w = n_tiles; n_full = S / BN; }
 
-  TileStage<D, BN, NT> sk, sv;
-  sk.fetch(kh, 0, S, tid);
-  sv.fetch(vh, 0, S, tid);
-  sk.commit(smem, tid);
-  sv.commit(smem + 2 * TILE_BYTES, tid);
+  const TileLoader<D, BN, 8> loader(lane, w);
+  loader.issue(kh, 0, S, smem);
+  loader.issue(vh, 0, S, smem + VREGION);
+  if (n_tiles > 1) { loader.issue(kh, BN, S, smem + TILE); loader.issue(vh, BN, S, smem + VREGION + TILE); }
+  if (n_tiles > 2) loader.issue(kh, 2 * BN, S, smem + 2 * TILE);
+  wait_tile_loads();
   __syncthreads();
 
+  const FwdLaneAddr<D> la(lane);
+  const uint32_t base = lds_base(smem);
+  // knext -> K buffer of tile j+1, vaddr -> V buffer of tile j during iteration j
+  uint32_t knext[KS], vaddr[DB][2];
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) knext[ks] = base + la.k[ks] + TILE;
+#pragma unroll
+  for (int db = 0; db < DB; db++) { vaddr[db][0] = base + VREGION + la.v[db][0]; vaddr[db][1] = base + VREGION + la.v[db][1]; }
+
+  f32x16 sa, sb;                 // S^T of the two 32-key halves of a tile
+  bf16x8 kop[KS];                // K operands of the next block to be scored
+  bf16x8 vop[DB];                // first V operands of the next P V block
+#pragma unroll
+  for (int db = 0; db < DB; db++) vop[db] = lds_tr_pair(vaddr[db][0], vaddr[db][1], 0);
+  if (n_w > 0) {
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    sa = zero;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) sa = mfma32(lds_b128(base + la.k[ks]), qf[ks], sa);
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) kop[ks] = lds_b128(base + la.k[ks], HALF);
+    if (n_w > 1) check_reference<DB>(max16(sa), c, st, oacc);   // tile 0 goes through the pipelined path
+  }
+  __syncthreads();   // everybody is done with K tile 0 before the loop overwrites its buffer
+
+  int r = 0;   // j % 3
   for (int j = 0; j < n_tiles; j++) {
-    const char* kt = smem + (j & 1) * TILE_BYTES;
-    const char* vt = smem + (2 + (j & 1)) * TILE_BYTES;
     const int k0 = j * BN;
-    const bool more = j + 1 < n_tiles;
-    if (more) {
-      sk.fetch(kh, k0 + BN, S, tid);
-      sv.fetch(vh, k0 + BN, S, tid);
-    }
-    if (!CAUSAL || k0 <= wave_qmax) {
-      // S^T blocks: rows = keys k0 + 32*kb + (0..31), columns = this wave's 32 queries
-      f32x16 sacc[2];
+    // copies run two tiles ahead: K(j+3) replaces K(j) (all its reads happened during
+    // iteration j-1), V(j+2) replaces V(j-1)
+    if (j + 3 < n_tiles) loader.issue(kh, k0 + 3 * BN, S, smem + r * TILE);
+    if (j + 2 < n_tiles) loader.issue(vh, k0 + 2 * BN, S, smem + VREGION + (r == 0 ? 2 : r - 1) * TILE);
+    const int k_step = (r == 1) ? -2 * TILE : TILE;   // K buffer of tile j+1 -> j+2
+    const int v_step = (r == 2) ? -2 * TILE : TILE;   // V buffer of tile j -> j+1
+
+    if (j < n_w - 1) {
+      // half a: score S_b(j) from kop | P_a(j) | O += V_a(j) P_a(j) | read K_a(j+1)
+      const float mb = half_step<D, 0, 0, false>(sa, sb, kop, vop, qf, knext, vaddr, v_step, oacc, c, st);
+      check_reference<DB>(mb, c, st, oacc);
+      // half b: score S_a(j+1) | P_b(j) | O += V_b(j) P_b(j) | read K_b(j+1); vaddr moves to V(j+1)
+      const float ma = half_step<D, HALF, HALF, true>(sb, sa, kop, vop, qf, knext, vaddr, v_step, oacc, c, st);
+      if (j + 1 < n_w - 1) check_reference<DB>(ma, c, st, oacc);   // the plain path masks first
+    } else {
+      if (j == n_w - 1) {
+        // plain path: the last tile of this wave (masked unless the sequence ends on a tile edge)
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        sb = zero;
 #pragma unroll
-      for (int kb = 0; kb < 2; kb++) {
-#pragma unroll
-        for (int e = 0; e < 16; e++) sacc[kb][e] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ks++)
-          sacc[kb] = mfma32(lds_operand<D>(kt, 32 * kb + n, ks, half), qf[ks], sacc[kb]);
-      }
-      const bool need_mask = CAUSAL ? (k0 + BN - 1 > wave_qmin) : (k0 + BN > S);
-      if (need_mask) {
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++)
+        for (int ks = 0; ks < KS; ks++) sb = mfma32(kop[ks], qf[ks], sb);
+        if (j >= n_full) {
 #pragma unroll
           for (int e = 0; e < 16; e++) {
-            const int key = k0 + 32 * kb + 8 * (e >> 2) + 4 * half + (e & 3);
-            const bool ok = CAUSAL ? (key <= my_q) : (key < S);
-            sacc[kb][e] = ok ? sacc[kb][e] : -INFINITY;
+            const int key = k0 + 8 * (e >> 2) + 4 * half + (e & 3);
+            sa[e] = (CAUSAL ? (key <= my_q) : (key < S)) ? sa[e] : -INFINITY;
+            sb[e] = (CAUSAL ? (key + 32 <= my_q) : (key + 32 < S)) ? sb[e] : -INFINITY;
           }
-      }
-      float tmax = sacc[0][0];
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) tmax = fmaxf(tmax, sacc[kb][e]);
-      tmax = half_max(tmax);
-      const float m_new = fmaxf(m, tmax);
-      if (__any(m_new > m)) {
-        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);   // 0 on the first tile
-        lsum *= alpha;
-#pragma unroll
-        for (int db = 0; db < DB; db++)
-#pragma unroll
-          for (int e = 0; e < 16; e++) oacc[db][e] *= alpha;
-        m = m_new;
-      }
-      const float mc = m * c;
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e], c, -mc));
-          sacc[kb][e] = p;
-          lsum += p;
         }
-      // O^T += V^T P^T, 16 keys per step
+        bf16x8 p[2];
+        check_reference<DB>(max16(sa), c, st, oacc);
+        exp_pack(sa, c, st, p);
+        pv_block<D>(vaddr, 0, p, oacc);
+        check_reference<DB>(max16(sb), c, st, oacc);
+        exp_pack(sb, c, st, p);
+        pv_block<D>(vaddr, HALF, p, oacc);
+      }
 #pragma unroll
-      for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-          const bf16x8 pb = pack_half(sacc[kb], t);
-#pragma unroll
-          for (int db = 0; db < DB; db++)
-            oacc[db] = mfma32(lds_operand_tr<D>(vt, 32 * kb + 16 * t, 32 * db, lane), pb, oacc[db]);
-        }
+      for (int db = 0; db < DB; db++) { vaddr[db][0] += v_step; vaddr[db][1] += v_step; }
     }
-    if (more) {
-      sk.commit(smem + ((j + 1) & 1) * TILE_BYTES, tid);
-      sv.commit(smem + (2 + ((j + 1) & 1)) * TILE_BYTES, tid);
-    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) knext[ks] += k_step;
+    // K(j+2) and V(j+1), issued one iteration ago, must have landed; this iteration's copies
+    // (2 + 2 instructions per wave) may stay in flight.
+    if (j + 3 < n_tiles) wait_tile_loads_except<2 * TileLoader<D, BN, 8>::N>();
+    else wait_tile_loads();
     __syncthreads();
+    r = (r == 2) ? 0 : r + 1;
   }
 
   // epilogue: normalise, store O (bf16) and LSE (natural log, scale included)
-  const float ltot = half_sum(lsum);
+  const float ltot = half_sum(st.lsum[0] + st.lsum[1]);
   const float inv = 1.f / ltot;
   if (my_q < S) {
     __bf16* orow = o + head_off + (size_t)my_q * D;
@@ -152,7 +336,7 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
         for (int e = 0; e < 4; e++) x[e] = oacc[db][4 * g + e] * inv;
         *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * g + 4 * half) = __builtin_convertvector(x, bf16x4);
       }
-    if (half == 0) lse[(size_t)tc.bh * S + my_q] = m * scale + __logf(ltot);
+    if (half == 0) lse[(size_t)tc.bh * S + my_q] = st.mref_c * kLn2 + __logf(ltot);
   }
 }
 
@@ -162,7 +346,7 @@ static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, void
   constexpr int BM = 256, BN = 64;
   const int T = (S + BM - 1) / BM;
   const int grid = 8 * ((BH + 7) / 8) * T;
-  const size_t lds = 4 * BN * D * 2;
+  const size_t lds = 6 * BN * D * 2;
   auto kern = fwd_kernel<D, CAUSAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;

@@ -86,6 +86,76 @@ struct TileStage {
   }
 };
 
+// Asynchronous global -> LDS copy of a [ROWS][D] bf16 tile without staging registers
+// (global_load_lds_dwordx4: lane i of a wave deposits its 16 bytes at lds_base + 16*i).
+// A wave copies 1 KB per instruction; the swizzle is applied by choosing WHICH global chunk
+// each lane fetches.  The common case costs no vector ALU work per tile: the lane's byte
+// offset inside a tile is fixed and the tile's base address travels in scalar registers.
+// Rows past the end of the sequence (last tile only) are clamped to the last row: every
+// consumer multiplies them by an exactly-zero probability or never stores their results.
+// The copies are issued as inline assembly on purpose: for the builtin the compiler assumes
+// that any later LDS read may alias the copy and waits for it at once, which would serialise
+// the copy of the next tile with the work on the current one.  The caller waits
+// (`wait_tile_loads*`) and then barriers before anyone reads the tile.
+template <int D, int ROWS, int NWAVES>
+struct TileLoader {
+  static constexpr int CH = D / 8;                        // 16-byte chunks per row
+  static constexpr int ROWS_PER_KB = 64 / CH;             // rows covered by one wave instruction
+  static constexpr int KB = ROWS / ROWS_PER_KB;           // 1 KB pieces in the tile
+  static constexpr int N = (KB + NWAVES - 1) / NWAVES;    // pieces per wave
+  static_assert(KB % NWAVES == 0, "every wave copies the same number of pieces");
+  int wave;
+  int row[N];          // tile row this lane fetches for piece i
+  uint32_t off[N];     // its byte offset inside the tile: row * 2D + 16 * (logical chunk)
+  __device__ __forceinline__ TileLoader(int lane, int wave_) : wave(wave_) {
+#pragma unroll
+    for (int i = 0; i < N; i++) {
+      const int piece = wave + NWAVES * i;
+      const int r = piece * ROWS_PER_KB + lane / CH;
+      row[i] = r;
+      off[i] = r * (D * 2) + (((lane % CH) ^ swizzle<D>(r)) << 4);
+    }
+  }
+  __device__ __forceinline__ void issue(const __bf16* head_base, int row0, int nrows, char* lds_tile) const {
+    const __bf16* tile_base = head_base + (size_t)row0 * D;   // scalar
+    const int last = nrows - 1 - row0;                         // last valid tile row (>= ROWS-1 unless ragged)
+#pragma unroll
+    for (int i = 0; i < N; i++) {
+      const uint32_t dst = __builtin_amdgcn_readfirstlane(
+          (uint32_t)(uintptr_t)HELIX_LDS(char, lds_tile + (wave + NWAVES * i) * 1024));
+      uint32_t o = off[i];
+      if (last < ROWS - 1) {   // wave-uniform, last tile of a ragged sequence only
+        const int rr = row[i] < last ? row[i] : last;
+        o -= (uint32_t)(row[i] - rr) * (D * 2);
+      }
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                   :: "v"(o), "s"(tile_base), "s"(dst) : "memory");
+    }
+  }
+};
+
+// s_waitcnt vmcnt(0) (expcnt and lgkmcnt left at their maxima).  Issued through the builtin so
+// that the compiler also learns that none of ITS vector memory loads is outstanding any more;
+// otherwise it re-waits on them inside the loops and thereby on the asynchronous tile copies.
+__device__ __forceinline__ void wait_tile_loads() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  asm volatile("" ::: "memory");
+}
+
+// s_waitcnt vmcnt(N): all but the N most recent vector memory operations of this wave are done.
+template <int N>
+__device__ __forceinline__ void wait_tile_loads_except() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+  asm volatile("" ::: "memory");
+}
+
+// Forces a value loaded from global memory to be complete at this point of the program.
+// Without it the compiler sinks such loads below the asynchronous tile copies and then
+// waits for both together in the middle of the main loop.
+template <typename T>
+__device__ __forceinline__ void pin(T& x) { asm volatile("" : "+v"(x)); }
+
 // MFMA operand whose 8 contraction slots are contiguous in memory: row `row`, elements
 // 16*ks + 8*half .. +7 of a swizzled LDS tile.
 template <int D>
