@@ -132,50 +132,68 @@ __device__ __forceinline__ void pv_block(const uint32_t (&vaddr)[D / 32][2], int
 }
 
 // One pipelined half step (see the header comment).  On entry s_cur is complete, kop holds
-// the K operands of the block to be scored now and vop[0..KS/2-1] the first V operands of
-// this step (rows V_IMM.. of the tile at vaddr); on exit s_next is complete, this lane's
-// maximum over its 16 entries of s_next is returned, kop holds the K operands at
-// knext + K_IMM and vop the first V operands of the next step.  When LAST_OF_TILE, the next
-// step reads the next V tile: vaddr moves on by v_step once this tile's reads are issued.
-// Every slot issues one MFMA and the LDS read of one operand needed KS/2 (V) or KS (K)
-// slots later.
-template <int D, int K_IMM, int V_IMM, bool LAST_OF_TILE>
+// the first KS/2 K operands of the block to be scored now and vop the first KS/2 V operands
+// of this step; on exit s_next is complete, this lane's maximum over its 16 entries of
+// s_next is returned, and kop / vop hold the first operands of the next step.  Every slot
+// issues one MFMA and the LDS read of the operand needed KS/2 slots later:
+//   score slots 0..KS/2-1   read K operand i + KS/2 of this block   (khi + K_CUR)
+//   P V slots 0..KS/2-1     read V operand i + KS/2 of this step    (vaddr + V_IMM + 16 rows)
+//   P V slots KS/2..KS-1    read K operand i - KS/2 of the next block (klo + K_NEXT) and
+//                           V operand i - KS/2 of the next step
+// The vector-ALU work is spread evenly: the 16 elements of P(h) (fma, exp2, row sum, bf16
+// pack) go to the score slots (elements 0..9) and to the first half of the P V slots
+// (elements 10..15, which the second half of the P V MFMAs consume); the row maximum of
+// S(h+1) fills the last P V slots.
+// When LAST_OF_TILE the next step works on the next V tile: vaddr moves on by v_step once this
+// tile's reads are issued.
+constexpr int kExpInScoreSlots = 10;
+template <int D, int K_CUR, int K_NEXT, int V_IMM, bool LAST_OF_TILE>
 __device__ __forceinline__ float half_step(const f32x16& s_cur, f32x16& s_next,
-                                           bf16x8 (&kop)[D / 16], bf16x8 (&vop)[D / 32], const bf16x8 (&qf)[D / 16],
-                                           const uint32_t (&knext)[D / 16], uint32_t (&vaddr)[D / 32][2], int v_step,
+                                           bf16x8 (&kop)[D / 32], bf16x8 (&vop)[D / 32], const bf16x8 (&qf)[D / 16],
+                                           const uint32_t (&klo)[D / 32], const uint32_t (&khi)[D / 32],
+                                           uint32_t (&vaddr)[D / 32][2], int v_step,
                                            f32x16 (&oacc)[D / 32], float c, SoftmaxState& st) {
-  constexpr int KS = D / 16, DB = D / 32, EPS = 16 / KS;   // EPS elements of P per slot
-  constexpr int RING = KS / 2;                              // V operands in flight (== DB)
+  constexpr int KS = D / 16, DB = D / 32;
+  constexpr int RING = KS / 2;                              // operands in flight (== DB)
   constexpr int HALF = 32 * D * 2;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  bf16x8 p[2];
-  f32x16 e;
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  float ev[16];     // exp2 values, each alive until its pair is packed
+  uint32_t pw[8];   // bf16 pairs of P
+  auto element = [&](int x) {
+    ev[x] = __builtin_amdgcn_exp2f(fmaf(s_cur[x], c, -st.mref_c));
+    st.lsum[x & 1] += ev[x];
+    if (x & 1) {
+      const f32x2 pr = {ev[x - 1], ev[x]};
+      pw[x / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+    }
+  };
 #pragma unroll
   for (int i = 0; i < KS; i++) {
-    s_next = mfma32(kop[i], qf[i], i == 0 ? zero : s_next);
+    s_next = mfma32(kop[i % RING], qf[i], i == 0 ? zero : s_next);
+    if (i < RING) kop[i] = lds_b128(khi[i], K_CUR);
 #pragma unroll
-    for (int x = EPS * i; x < EPS * (i + 1); x++) {
-      e[x] = __builtin_amdgcn_exp2f(fmaf(s_cur[x], c, -st.mref_c));
-      st.lsum[x & 1] += e[x];
-    }
-    if (i == KS / 2 - 1) p[0] = pack_half(e, 0);
-    if (i == KS - 1) p[1] = pack_half(e, 1);
+    for (int x = 0; x < kExpInScoreSlots; x++)
+      if (x * KS / kExpInScoreSlots == i) element(x);
     __builtin_amdgcn_sched_barrier(0);
   }
   float m0 = 0.f, m1 = 0.f, m2 = 0.f, m3 = 0.f, m4 = 0.f;
 #pragma unroll
   for (int i = 0; i < KS; i++) {
-    oacc[i % DB] = mfma32(vop[i % RING], p[i / DB], oacc[i % DB]);
+    const u32x4 pk = {pw[4 * (i / DB)], pw[4 * (i / DB) + 1], pw[4 * (i / DB) + 2], pw[4 * (i / DB) + 3]};
+    oacc[i % DB] = mfma32(vop[i % RING], __builtin_bit_cast(bf16x8, pk), oacc[i % DB]);
     if (i < RING) {
-      // V operand i + RING of this step (the second 16 keys)
-      vop[i % RING] = lds_tr_pair(vaddr[i % DB][0], vaddr[i % DB][1], V_IMM + 16 * D * 2);
+      vop[i] = lds_tr_pair(vaddr[i][0], vaddr[i][1], V_IMM + 16 * D * 2);
+#pragma unroll
+      for (int x = kExpInScoreSlots; x < 16; x++)
+        if ((x - kExpInScoreSlots) * RING / (16 - kExpInScoreSlots) == i) element(x);
     } else {
-      // V operand i - RING of the next step
-      if (LAST_OF_TILE) { vaddr[i % DB][0] += v_step; vaddr[i % DB][1] += v_step; }
-      vop[i % RING] = lds_tr_pair(vaddr[i % DB][0], vaddr[i % DB][1], LAST_OF_TILE ? 0 : V_IMM + HALF);
+      if (LAST_OF_TILE) { vaddr[i - RING][0] += v_step; vaddr[i - RING][1] += v_step; }
+      vop[i - RING] = lds_tr_pair(vaddr[i - RING][0], vaddr[i - RING][1], LAST_OF_TILE ? 0 : V_IMM + HALF);
+      kop[i - RING] = lds_b128(klo[i - RING], K_NEXT);
     }
-    kop[i] = lds_b128(knext[i], K_IMM);
-    // row maximum of s_next, spread over the later slots (the score MFMAs have drained by then)
+    // row maximum of s_next in the last slots (the score MFMAs have drained by then)
     if (i == KS - 4) { m0 = fmaxf(fmaxf(s_next[0], s_next[1]), s_next[2]); m1 = fmaxf(fmaxf(s_next[3], s_next[4]), s_next[5]); pin(m0); pin(m1); }
     if (i == KS - 3) { m2 = fmaxf(fmaxf(s_next[6], s_next[7]), s_next[8]); m3 = fmaxf(fmaxf(s_next[9], s_next[10]), s_next[11]); pin(m2); pin(m3); }
     if (i == KS - 2) { m4 = fmaxf(fmaxf(s_next[12], s_next[13]), s_next[14]); m0 = fmaxf(fmaxf(m0, m1), s_next[15]); pin(m4); pin(m0); }
@@ -194,12 +212,13 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   constexpr int DB = D / 32;   // 32-wide blocks of the head dimension
   constexpr int TILE = BN * D * 2;
   constexpr int HALF = 32 * D * 2;   // bytes of 32 key rows
-  constexpr int VREGION = 3 * TILE;
-  extern __shared__ __align__(16) char smem[];   // K[3] then V[3]; tile j lives in buffer j % 3
+  constexpr int VREGION = 4 * TILE;
+  extern __shared__ __align__(16) char smem[];   // K[4] then V[3]; K tile j in buffer j % 4, V tile j in j % 3
 
   const TileCoord tc = map_block(blockIdx.x, BH, T, true);
   if (!tc.valid) return;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, held in a scalar register
   const int half = lane >> 5, n = lane & 31;
   const int q0 = tc.tile * BM;
   const int my_q = q0 + 32 * w + n;
@@ -207,7 +226,8 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   const __bf16* qh = q + head_off;
   const __bf16* kh = k + head_off;
   const __bf16* vh = v + head_off;
-  const float c = scale * kLog2e;
+  const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, scale * kLog2e)));
+  const uint32_t base = lds_base(smem);
 
   bf16x8 qf[KS];
   {
@@ -237,24 +257,24 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   else { n_w = n_tiles; n_full = S / BN; }
 
   const TileLoader<D, BN, 8> loader(lane, w);
-  loader.issue(kh, 0, S, smem);
-  loader.issue(vh, 0, S, smem + VREGION);
-  if (n_tiles > 1) { loader.issue(kh, BN, S, smem + TILE); loader.issue(vh, BN, S, smem + VREGION + TILE); }
-  if (n_tiles > 2) loader.issue(kh, 2 * BN, S, smem + 2 * TILE);
+  loader.issue(kh, 0, S, base);
+  loader.issue(vh, 0, S, base + VREGION);
+  if (n_tiles > 1) { loader.issue(kh, BN, S, base + TILE); loader.issue(vh, BN, S, base + VREGION + TILE); }
+  if (n_tiles > 2) loader.issue(kh, 2 * BN, S, base + 2 * TILE);
   wait_tile_loads();
   __syncthreads();
 
   const FwdLaneAddr<D> la(lane);
-  const uint32_t base = lds_base(smem);
-  // knext -> K buffer of tile j+1, vaddr -> V buffer of tile j during iteration j
-  uint32_t knext[KS], vaddr[DB][2];
+  // Lane addresses: klo = contraction steps 0..KS/2-1 of the K tile the NEXT block comes from,
+  // khi = steps KS/2..KS-1 of the tile the CURRENT block comes from, vaddr = current V tile.
+  uint32_t klo[DB], khi[DB], vaddr[DB][2];
 #pragma unroll
-  for (int ks = 0; ks < KS; ks++) knext[ks] = base + la.k[ks] + TILE;
+  for (int i = 0; i < DB; i++) { klo[i] = base + la.k[i] + TILE; khi[i] = base + la.k[i + DB]; }
 #pragma unroll
   for (int db = 0; db < DB; db++) { vaddr[db][0] = base + VREGION + la.v[db][0]; vaddr[db][1] = base + VREGION + la.v[db][1]; }
 
   f32x16 sa, sb;                 // S^T of the two 32-key halves of a tile
-  bf16x8 kop[KS];                // K operands of the next block to be scored
+  bf16x8 kop[DB];                // first K operands of the next block to be scored
   bf16x8 vop[DB];                // first V operands of the next P V block
 #pragma unroll
   for (int db = 0; db < DB; db++) vop[db] = lds_tr_pair(vaddr[db][0], vaddr[db][1], 0);
@@ -264,62 +284,79 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) sa = mfma32(lds_b128(base + la.k[ks]), qf[ks], sa);
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++) kop[ks] = lds_b128(base + la.k[ks], HALF);
+    for (int i = 0; i < DB; i++) kop[i] = lds_b128(base + la.k[i], HALF);
     if (n_w > 1) check_reference<DB>(max16(sa), c, st, oacc);   // tile 0 goes through the pipelined path
   }
-  __syncthreads();   // everybody is done with K tile 0 before the loop overwrites its buffer
 
-  int r = 0;   // j % 3
-  for (int j = 0; j < n_tiles; j++) {
-    const int k0 = j * BN;
-    // copies run two tiles ahead: K(j+3) replaces K(j) (all its reads happened during
+  // The tile sweep is split per wave into the pipelined tiles 0 .. n_w-2 and a second loop
+  // with the wave's last tile (plain path) and the tiles it only helps to copy.  Every wave
+  // of the workgroup runs n_tiles iterations in total and meets the others at the barriers.
+  int rk = 0, rv = 0;   // j % 4, j % 3
+  int j = 0;
+  auto copy_ahead = [&]() {
+    // copies run two tiles ahead: K(j+3) replaces K(j-1) (last read in the first half of
     // iteration j-1), V(j+2) replaces V(j-1)
-    if (j + 3 < n_tiles) loader.issue(kh, k0 + 3 * BN, S, smem + r * TILE);
-    if (j + 2 < n_tiles) loader.issue(vh, k0 + 2 * BN, S, smem + VREGION + (r == 0 ? 2 : r - 1) * TILE);
-    const int k_step = (r == 1) ? -2 * TILE : TILE;   // K buffer of tile j+1 -> j+2
-    const int v_step = (r == 2) ? -2 * TILE : TILE;   // V buffer of tile j -> j+1
-
-    if (j < n_w - 1) {
-      // half a: score S_b(j) from kop | P_a(j) | O += V_a(j) P_a(j) | read K_a(j+1)
-      const float mb = half_step<D, 0, 0, false>(sa, sb, kop, vop, qf, knext, vaddr, v_step, oacc, c, st);
-      check_reference<DB>(mb, c, st, oacc);
-      // half b: score S_a(j+1) | P_b(j) | O += V_b(j) P_b(j) | read K_b(j+1); vaddr moves to V(j+1)
-      const float ma = half_step<D, HALF, HALF, true>(sb, sa, kop, vop, qf, knext, vaddr, v_step, oacc, c, st);
-      if (j + 1 < n_w - 1) check_reference<DB>(ma, c, st, oacc);   // the plain path masks first
-    } else {
-      if (j == n_w - 1) {
-        // plain path: the last tile of this wave (masked unless the sequence ends on a tile edge)
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        sb = zero;
-#pragma unroll
-        for (int ks = 0; ks < KS; ks++) sb = mfma32(kop[ks], qf[ks], sb);
-        if (j >= n_full) {
-#pragma unroll
-          for (int e = 0; e < 16; e++) {
-            const int key = k0 + 8 * (e >> 2) + 4 * half + (e & 3);
-            sa[e] = (CAUSAL ? (key <= my_q) : (key < S)) ? sa[e] : -INFINITY;
-            sb[e] = (CAUSAL ? (key + 32 <= my_q) : (key + 32 < S)) ? sb[e] : -INFINITY;
-          }
-        }
-        bf16x8 p[2];
-        check_reference<DB>(max16(sa), c, st, oacc);
-        exp_pack(sa, c, st, p);
-        pv_block<D>(vaddr, 0, p, oacc);
-        check_reference<DB>(max16(sb), c, st, oacc);
-        exp_pack(sb, c, st, p);
-        pv_block<D>(vaddr, HALF, p, oacc);
-      }
-#pragma unroll
-      for (int db = 0; db < DB; db++) { vaddr[db][0] += v_step; vaddr[db][1] += v_step; }
-    }
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++) knext[ks] += k_step;
+    if (j + 3 < n_tiles) loader.issue(kh, (j + 3) * BN, S, base + ((rk + 3) & 3) * TILE);
+    if (j + 2 < n_tiles) loader.issue(vh, (j + 2) * BN, S, base + VREGION + (rv == 0 ? 2 : rv - 1) * TILE);
+  };
+  auto finish_tile = [&]() {
     // K(j+2) and V(j+1), issued one iteration ago, must have landed; this iteration's copies
     // (2 + 2 instructions per wave) may stay in flight.
     if (j + 3 < n_tiles) wait_tile_loads_except<2 * TileLoader<D, BN, 8>::N>();
     else wait_tile_loads();
     __syncthreads();
-    r = (r == 2) ? 0 : r + 1;
+    rk = (rk + 1) & 3;
+    rv = (rv == 2) ? 0 : rv + 1;
+  };
+
+  for (; j < n_w - 1; j++) {
+    copy_ahead();
+    const int khi_step = (rk == 3) ? -3 * TILE : TILE;   // K buffer of tile j   -> j+1
+    const int klo_step = (rk == 2) ? -3 * TILE : TILE;   // K buffer of tile j+1 -> j+2
+    const int v_step = (rv == 2) ? -2 * TILE : TILE;     // V buffer of tile j   -> j+1
+    // half a: score S_b(j) | P_a(j) | O += V_a(j) P_a(j) | read K_b(j) 4..7, K_a(j+1) 0..3
+    const float mb = half_step<D, HALF, 0, 0, false>(sa, sb, kop, vop, qf, klo, khi, vaddr, v_step, oacc, c, st);
+    check_reference<DB>(mb, c, st, oacc);
+#pragma unroll
+    for (int i = 0; i < DB; i++) khi[i] += khi_step;
+    // half b: score S_a(j+1) | P_b(j) | O += V_b(j) P_b(j) | read K_a(j+1) 4..7, K_b(j+1) 0..3;
+    // vaddr moves to V(j+1)
+    const float ma = half_step<D, 0, HALF, HALF, true>(sb, sa, kop, vop, qf, klo, khi, vaddr, v_step, oacc, c, st);
+    if (j + 1 < n_w - 1) check_reference<DB>(ma, c, st, oacc);   // the plain path masks first
+#pragma unroll
+    for (int i = 0; i < DB; i++) klo[i] += klo_step;
+    finish_tile();
+  }
+
+  for (; j < n_tiles; j++) {
+    copy_ahead();
+    if (j == n_w - 1) {
+      // plain path: the last tile of this wave (masked unless the sequence ends on a tile edge);
+      // kop holds steps 0..KS/2-1 of K_b(j), khi points at K(j), vaddr at V(j)
+      const int k0 = j * BN;
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      sb = zero;
+#pragma unroll
+      for (int i = 0; i < DB; i++) sb = mfma32(kop[i], qf[i], sb);
+#pragma unroll
+      for (int i = 0; i < DB; i++) sb = mfma32(lds_b128(khi[i], HALF), qf[i + DB], sb);
+      if (j >= n_full) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int key = k0 + 8 * (e >> 2) + 4 * half + (e & 3);
+          sa[e] = (CAUSAL ? (key <= my_q) : (key < S)) ? sa[e] : -INFINITY;
+          sb[e] = (CAUSAL ? (key + 32 <= my_q) : (key + 32 < S)) ? sb[e] : -INFINITY;
+        }
+      }
+      bf16x8 p[2];
+      check_reference<DB>(max16(sa), c, st, oacc);
+      exp_pack(sa, c, st, p);
+      pv_block<D>(vaddr, 0, p, oacc);
+      check_reference<DB>(max16(sb), c, st, oacc);
+      exp_pack(sb, c, st, p);
+      pv_block<D>(vaddr, HALF, p, oacc);
+    }
+    finish_tile();
   }
 
   // epilogue: normalise, store O (bf16) and LSE (natural log, scale included)
@@ -346,7 +383,7 @@ static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, void
   constexpr int BM = 256, BN = 64;
   const int T = (S + BM - 1) / BM;
   const int grid = 8 * ((BH + 7) / 8) * T;
-  const size_t lds = 6 * BN * D * 2;
+  const size_t lds = 7 * BN * D * 2;
   auto kern = fwd_kernel<D, CAUSAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;

@@ -104,32 +104,37 @@ struct TileLoader {
   static constexpr int KB = ROWS / ROWS_PER_KB;           // 1 KB pieces in the tile
   static constexpr int N = (KB + NWAVES - 1) / NWAVES;    // pieces per wave
   static_assert(KB % NWAVES == 0, "every wave copies the same number of pieces");
-  int wave;
-  int row[N];          // tile row this lane fetches for piece i
-  uint32_t off[N];     // its byte offset inside the tile: row * 2D + 16 * (logical chunk)
-  __device__ __forceinline__ TileLoader(int lane, int wave_) : wave(wave_) {
+  int wave, lane_row;  // lane_row: this lane's row inside a piece
+  uint32_t off[N];     // byte offset inside the tile of the chunk this lane fetches for piece i:
+                       // row * 2D + 16 * (logical chunk)
+  __device__ __forceinline__ TileLoader(int lane, int wave_) : wave(wave_), lane_row(lane / CH) {
 #pragma unroll
     for (int i = 0; i < N; i++) {
-      const int piece = wave + NWAVES * i;
-      const int r = piece * ROWS_PER_KB + lane / CH;
-      row[i] = r;
+      const int r = (wave + NWAVES * i) * ROWS_PER_KB + lane_row;
       off[i] = r * (D * 2) + (((lane % CH) ^ swizzle<D>(r)) << 4);
     }
   }
-  __device__ __forceinline__ void issue(const __bf16* head_base, int row0, int nrows, char* lds_tile) const {
+  // lds_tile_addr: 32-bit LDS address of the destination tile (wave-uniform).
+  __device__ __forceinline__ void issue(const __bf16* head_base, int row0, int nrows, uint32_t lds_tile_addr) const {
     const __bf16* tile_base = head_base + (size_t)row0 * D;   // scalar
     const int last = nrows - 1 - row0;                         // last valid tile row (>= ROWS-1 unless ragged)
+    if (last >= ROWS - 1) {
 #pragma unroll
-    for (int i = 0; i < N; i++) {
-      const uint32_t dst = __builtin_amdgcn_readfirstlane(
-          (uint32_t)(uintptr_t)HELIX_LDS(char, lds_tile + (wave + NWAVES * i) * 1024));
-      uint32_t o = off[i];
-      if (last < ROWS - 1) {   // wave-uniform, last tile of a ragged sequence only
-        const int rr = row[i] < last ? row[i] : last;
-        o -= (uint32_t)(row[i] - rr) * (D * 2);
+      for (int i = 0; i < N; i++) {
+        const uint32_t dst = lds_tile_addr + (wave + NWAVES * i) * 1024;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :: "v"(off[i]), "s"(tile_base), "s"(dst) : "memory");
       }
-      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                   :: "v"(o), "s"(tile_base), "s"(dst) : "memory");
+    } else {   // last tile of a ragged sequence: clamp the row
+#pragma unroll
+      for (int i = 0; i < N; i++) {
+        const uint32_t dst = lds_tile_addr + (wave + NWAVES * i) * 1024;
+        const int row = (wave + NWAVES * i) * ROWS_PER_KB + lane_row;
+        const int rr = row < last ? row : last;
+        const uint32_t o = off[i] - (uint32_t)(row - rr) * (D * 2);
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :: "v"(o), "s"(tile_base), "s"(dst) : "memory");
+      }
     }
   }
 };
