@@ -48,23 +48,6 @@ struct FwdLaneAddr {
   }
 };
 
-// LDS reads take an absolute 32-bit LDS address held in a register plus a compile-time
-// immediate that folds into the instruction's offset field.
-__device__ __forceinline__ uint32_t lds_base(const char* smem) { return (uint32_t)(uintptr_t)HELIX_LDS(const char, smem); }
-__device__ __forceinline__ bf16x8 lds_b128(uint32_t addr, int imm = 0) {
-  return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
-      reinterpret_cast<const __attribute__((address_space(3))) char*>((uintptr_t)addr) + imm);
-}
-
-// V^T operand: 16 keys (two groups of 4+4 rows per lane half) x 32 head-dim columns.
-__device__ __forceinline__ bf16x8 lds_tr_pair(uint32_t addr0, uint32_t addr1, int imm) {
-  typedef __attribute__((address_space(3))) char* lds_ptr;
-  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HELIX_LDS(s16x4, reinterpret_cast<lds_ptr>((uintptr_t)addr0) + imm));
-  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HELIX_LDS(s16x4, reinterpret_cast<lds_ptr>((uintptr_t)addr1) + imm));
-  const s16x8 ab = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, ab);
-}
-
 __device__ __forceinline__ float max16(const f32x16& s) {
   float a = fmaxf(fmaxf(s[0], s[1]), s[2]);
   float b = fmaxf(fmaxf(s[3], s[4]), s[5]);

@@ -97,6 +97,15 @@ struct TileStage {
 // that any later LDS read may alias the copy and waits for it at once, which would serialise
 // the copy of the next tile with the work on the current one.  The caller waits
 // (`wait_tile_loads*`) and then barriers before anyone reads the tile.
+// A pointer the caller knows to be wave-uniform, moved into scalar registers.
+template <typename T>
+__device__ __forceinline__ const T* uniform_ptr(const T* p) {
+  const uint64_t x = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+  return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
+}
+
 template <int D, int ROWS, int NWAVES>
 struct TileLoader {
   static constexpr int CH = D / 8;                        // 16-byte chunks per row
@@ -116,19 +125,19 @@ struct TileLoader {
   }
   // lds_tile_addr: 32-bit LDS address of the destination tile (wave-uniform).
   __device__ __forceinline__ void issue(const __bf16* head_base, int row0, int nrows, uint32_t lds_tile_addr) const {
-    const __bf16* tile_base = head_base + (size_t)row0 * D;   // scalar
-    const int last = nrows - 1 - row0;                         // last valid tile row (>= ROWS-1 unless ragged)
+    const __bf16* tile_base = uniform_ptr(head_base + (size_t)row0 * D);
+    const int last = __builtin_amdgcn_readfirstlane(nrows - 1 - row0);   // last valid tile row (>= ROWS-1 unless ragged)
     if (last >= ROWS - 1) {
 #pragma unroll
       for (int i = 0; i < N; i++) {
-        const uint32_t dst = lds_tile_addr + (wave + NWAVES * i) * 1024;
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile_addr + (wave + NWAVES * i) * 1024);
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                      :: "v"(off[i]), "s"(tile_base), "s"(dst) : "memory");
       }
     } else {   // last tile of a ragged sequence: clamp the row
 #pragma unroll
       for (int i = 0; i < N; i++) {
-        const uint32_t dst = lds_tile_addr + (wave + NWAVES * i) * 1024;
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile_addr + (wave + NWAVES * i) * 1024);
         const int row = (wave + NWAVES * i) * ROWS_PER_KB + lane_row;
         const int rr = row < last ? row : last;
         const uint32_t o = off[i] - (uint32_t)(row - rr) * (D * 2);
@@ -153,6 +162,23 @@ __device__ __forceinline__ void wait_tile_loads_except() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
   asm volatile("" ::: "memory");
+}
+
+// LDS reads take an absolute 32-bit LDS address held in a register plus a compile-time
+// immediate that folds into the instruction's offset field.
+__device__ __forceinline__ uint32_t lds_base(const char* smem) { return (uint32_t)(uintptr_t)HELIX_LDS(const char, smem); }
+__device__ __forceinline__ bf16x8 lds_b128(uint32_t addr, int imm = 0) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+      reinterpret_cast<const __attribute__((address_space(3))) char*>((uintptr_t)addr) + imm);
+}
+
+// V^T operand: 16 keys (two groups of 4+4 rows per lane half) x 32 head-dim columns.
+__device__ __forceinline__ bf16x8 lds_tr_pair(uint32_t addr0, uint32_t addr1, int imm) {
+  typedef __attribute__((address_space(3))) char* lds_ptr;
+  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HELIX_LDS(s16x4, reinterpret_cast<lds_ptr>((uintptr_t)addr0) + imm));
+  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HELIX_LDS(s16x4, reinterpret_cast<lds_ptr>((uintptr_t)addr1) + imm));
+  const s16x8 ab = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, ab);
 }
 
 // Forces a value loaded from global memory to be complete at this point of the program.
