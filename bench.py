@@ -28,7 +28,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="workload id 1..5 (default 4: the metric's workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=12288)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=49152)
     return ap.parse_args()
 
 
