@@ -21,8 +21,10 @@
 //     slots  8..15   dP(b+1)          |   (one element per slot)
 //     slots 16..23   dV^T += ..P(b)   | P(b+1) = exp2(S(b+1)*c - LSE*log2e)
 //     slots 24..31   dK^T += ..dS(b)  |   (one element per slot)
-// Q / dO / LSE / delta tiles are copied global -> LDS asynchronously two tiles ahead into
-// three stages; one workgroup barrier per 64-row tile.  Blocks cut by the causal diagonal
+// Q / dO / LSE / delta tiles are copied global -> LDS asynchronously into four stages: while
+// tile t is worked on, tile t+1 (which the second step of the iteration already reads) is
+// resident too, tile t+2 may still be landing and tile t+3 is being issued; one workgroup
+// barrier per 64-row tile.  Blocks cut by the causal diagonal
 // (the first two tiles of every key tile) and a ragged last tile run through a plain,
 // masked path.  No atomics: every dK / dV element is produced by exactly one lane.
 #include "helix_common.hpp"
@@ -59,7 +61,7 @@ struct Geometry {
   static constexpr int ROWS32 = 32 * D * 2;          // bytes of 32 rows
   static constexpr int STATS = 2 * TILE;             // per-wave copies of LSE[64], delta[64] follow Q, dO
   static constexpr int STAGE = 2 * TILE + 4 * 512;
-  static constexpr int NSTAGE = 3;
+  static constexpr int NSTAGE = 4;
 };
 
 // Lane state of the pipelined path.
@@ -214,7 +216,7 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
 
   const TileLoader<D, BM, 4> loader(lane, w);
   constexpr int NDMA = 2 * TileLoader<D, BM, 4>::N + 2;      // copy instructions per wave and tile
-  int t = 0, st = 0;                                          // tile and its stage (t % 3)
+  int t = 0, st = 0;                                          // tile and its stage (t % 4)
   auto copy_tile = [&](int tt, int stage) {
     const uint32_t sb = base + stage * G::STAGE;
     const int row0 = m_start + tt * BM;
@@ -226,16 +228,19 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
     dma_dword(delta_h, (uint32_t)r * 4, sb + G::STATS + w * 512 + 256);
   };
   auto copy_ahead = [&]() {
-    if (t + 2 < nt) copy_tile(t + 2, st == 0 ? 2 : st - 1);
+    if (t + 3 < nt) copy_tile(t + 3, (st + 3) & 3);   // replaces tile t-1
   };
   auto finish_tile = [&]() {
-    if (t + 2 < nt) wait_tile_loads_except<NDMA>();   // tile t+1 has landed, tile t+2 may be in flight
+    // tiles up to t+2 must have landed before the next iteration starts (it reads t+1 and
+    // t+2); the copy of tile t+3 issued in this iteration may stay in flight
+    if (t + 3 < nt) wait_tile_loads_except<NDMA>();
     else wait_tile_loads();
     __syncthreads();
-    st = (st == 2) ? 0 : st + 1;
+    st = (st + 1) & 3;
   };
   copy_tile(0, 0);
   if (nt > 1) copy_tile(1, 1);
+  if (nt > 2) copy_tile(2, 2);
   wait_tile_loads();
   __syncthreads();
 
@@ -328,7 +333,7 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
     }
     for (; t < t_hi; t++) {
       copy_ahead();
-      const int stage_step = (st == 2) ? -2 * G::STAGE : G::STAGE;
+      const int stage_step = (st == 3) ? -3 * G::STAGE : G::STAGE;
       dkdv_step<D, false>(spA, dpA, spB, dpB, pp, kf, vf, dkacc, dvacc, stage_step, c);
       dkdv_step<D, true>(spB, dpB, spA, dpA, pp, kf, vf, dkacc, dvacc, stage_step, c);
       finish_tile();
