@@ -6,8 +6,10 @@
 //   dkdv       : (bwd_dkdv.hip) a workgroup owns 128 keys and sweeps the query tiles that see
 //                them: S = Q K^T, P = exp(scale*S - LSE), dV^T += dO^T P, dP = dO V^T,
 //                dS = P o (dP - delta), dK^T += Q^T dS
-//   dq         : a workgroup owns 256 queries and sweeps the visible key tiles:
+//   dq         : (bwd_dq.hip) a workgroup owns 256 queries and sweeps the visible key tiles:
 //                S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T
+//   delta_head : the unpipelined variant of the dQ sweep kept in this file; it only produces
+//                delta_i = sum_j p_ij dp_ij for the first rows of every head
 //
 // Every output element is produced by exactly one lane, so there are no atomics and the
 // result is bit-reproducible.
@@ -202,15 +204,6 @@ static hipError_t launch_dq_t(const void* q, const void* k, const void* v, const
   hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, stream, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v,
                      (const __bf16*)dO, lse, delta, (__bf16*)dq, delta_out, BH, S, T, scale);
   return hipGetLastError();
-}
-
-hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void* dO,
-                         const float* lse, const float* delta, void* dq,
-                         int BH, int S, int D, float scale, bool causal, hipStream_t stream) {
-  if (D == 128) return causal ? launch_dq_t<128, true, false>(q, k, v, dO, lse, delta, dq, nullptr, BH, S, S, scale, stream)
-                              : launch_dq_t<128, false, false>(q, k, v, dO, lse, delta, dq, nullptr, BH, S, S, scale, stream);
-  return causal ? launch_dq_t<64, true, false>(q, k, v, dO, lse, delta, dq, nullptr, BH, S, S, scale, stream)
-                : launch_dq_t<64, false, false>(q, k, v, dO, lse, delta, dq, nullptr, BH, S, S, scale, stream);
 }
 
 hipError_t launch_bwd_delta_head(const void* q, const void* k, const void* v, const void* dO,
