@@ -19,6 +19,13 @@ import numpy as np
 
 PEAK_FLOP_PER_CLK_PER_CU = 4096          # dense bf16 MFMA, 4 SIMDs x 1024
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch at config 4 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
+# copy-kernel calibration (profiles/hbm_traffic_cfg4.md): fetched x2.00 + written x1.00.
+TRAFFIC_CFG4_BYTES = {"fwd": (1.01e7 * 2 + 1.065e6) * 1024, "dkdv": (1.86e7 * 2 + 2.097e6) * 1024,
+                      "dq": (1.25e7 * 2 + 1.049e6) * 1024}
+# Sustained rate of a pure v_mfma_f32_32x32x16_bf16 loop on the same chip (profiles/kernel_stats_cfg4.md):
+# the clock drops under the power limit when the operands are random.
+SUSTAINED_MFMA_TFLOPS = {"constant_operands": 2250.0, "random_operands": 1760.0}
 
 
 def parse():
@@ -128,10 +135,14 @@ def main():
         "bwd_tflops": 10 * unit / (ms_bwd * 1e-3) / 1e12,
         "fwd_bwd_tflops_table1_convention": 12 * unit / (wall / args.steps) / 1e12,
         "kernel_ms": ms,
+        "executed_tflops": {"fwd": 4 * unit / (ms["fwd"] * 1e-3) / 1e12, "dkdv": 8 * unit / (ms["dkdv"] * 1e-3) / 1e12,
+                            "dq": 6 * unit / (ms["dq"] * 1e-3) / 1e12},
+        "sustained_mfma_tflops_measured": SUSTAINED_MFMA_TFLOPS,
         "preprocess_gbs": pre_bytes / (ms["preprocess"] * 1e-3) / 1e9,
         "preprocess_frac_of_hbm_peak": pre_bytes / (ms["preprocess"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "mfma", "kernel": dom[0], "achieved": dom_tflops, "peak": 2500.0, "unit": "TFLOP/s",
-                     "frac": dom_tflops / 2500.0, "traffic": None,
+                     "frac": dom_tflops / 2500.0,
+                     "traffic": TRAFFIC_CFG4_BYTES.get(dom[0]) if cfg.cfg_id == 4 else None,
                      "flops_per_launch": dom[1] * unit, "avg_launch_ms": ms[dom[0]]},
     }
     if not args.no_cpu_baseline:
