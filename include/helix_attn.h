@@ -46,8 +46,24 @@ typedef enum {
   HELIX_ERR_MISALIGNED = 4,
   HELIX_ERR_BAD_SCALE = 5,
   HELIX_ERR_WORKSPACE = 6,
-  HELIX_ERR_LAUNCH = 7
+  HELIX_ERR_LAUNCH = 7,
+  HELIX_ERR_BAD_STRIDE = 8
 } helix_status;
+
+/* Element strides of a logical [B, H, S, D] bf16 tensor whose D elements per row are
+ * contiguous: element (b, h, s, d) lives at base + b*batch + h*head + s*row + d.  Used by
+ * the *_strided entry points; a NULL helix_strides pointer there means contiguous
+ * [B, H, S, D] (batch = H*S*D, head = S*D, row = D).  Host memory, read during the call.
+ * Accepted strides: non-negative multiples of 8 elements (rows start on 16-byte
+ * boundaries), D <= row <= 2^24, and nested -- ordered by stride, each dimension of extent
+ * > 1 steps over at least the whole span of the next smaller one -- which every permutation
+ * of the dimensions of a dense or padded buffer satisfies and which excludes overlap.
+ * Anything else is HELIX_ERR_BAD_STRIDE. */
+typedef struct helix_strides {
+  long long batch;
+  long long head;
+  long long row;
+} helix_strides;
 
 /* Forward (Table 1, Attention column, "Forward": two matrix products per (query, key)
  * pair, 4*b*h*s^2 FLOPs for a full score matrix).
@@ -105,6 +121,36 @@ int helix_attn_device_info(int* compute_units, int* clock_khz);
 
 /* Human-readable name of a helix_status value (static storage, never NULL). */
 const char* helix_status_string(int status);
+
+/* Forward and backward on strided views.  The paper's activations are sequence-major
+ * [s, b, h] tensors (Section 2.1), attention consumes the Q, K, V produced by the QKV linear
+ * layer (Section 4.2) and, under sequence parallelism, each GPU works on h/t of the heads
+ * over the full sequence (Section 2.2): with these entry points q, k, v can be views into
+ * the [S, B, 3*H*D] (or per-head interleaved [S, B, H, 3*D]) output of that layer and
+ * o, dO, dq, dk, dv views of [S, B, H*D] activations, with no transposing copy.
+ * Same semantics, argument rules and error behaviour as helix_attn_fwd / helix_attn_bwd;
+ * every *_strides argument is a host pointer or NULL (see helix_strides).  lse and the
+ * workspace stay contiguous fp32 [B, H, S]. */
+int helix_attn_fwd_strided(const void* q, const helix_strides* q_strides,
+                           const void* k, const helix_strides* k_strides,
+                           const void* v, const helix_strides* v_strides,
+                           void* o, const helix_strides* o_strides, float* lse,
+                           int B, int H, int S, int D, float scale, int causal, void* stream);
+int helix_attn_bwd_strided(const void* q, const helix_strides* q_strides,
+                           const void* k, const helix_strides* k_strides,
+                           const void* v, const helix_strides* v_strides,
+                           const void* o, const helix_strides* o_strides, const float* lse,
+                           const void* dO, const helix_strides* dO_strides,
+                           void* dq, const helix_strides* dq_strides,
+                           void* dk, const helix_strides* dk_strides,
+                           void* dv, const helix_strides* dv_strides,
+                           void* workspace, size_t workspace_bytes,
+                           int B, int H, int S, int D, float scale, int causal, void* stream);
+
+/* Whether `strides` (NULL: contiguous) is acceptable for a [B, H, S, D] view: HELIX_OK,
+ * HELIX_ERR_BAD_STRIDE, or the shape errors of the other calls.  Pure host arithmetic: the
+ * same check the *_strided entry points apply to each of their tensors. */
+int helix_attn_check_strides(const helix_strides* strides, int B, int H, int S, int D);
 
 /* Library version: major*10000 + minor*100 + patch. */
 int helix_attn_version(void);

@@ -13,11 +13,17 @@ import pathlib
 import torch
 
 LIB_PATH = pathlib.Path(__file__).resolve().parent / "csrc" / "libhelix_attn.so"
-EXPORTS = ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_bwd_workspace_bytes",
+EXPORTS = ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_fwd_strided", "helix_attn_bwd_strided",
+           "helix_attn_check_strides", "helix_attn_bwd_workspace_bytes",
            "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head", "helix_attn_bwd_dkdv", "helix_attn_bwd_dq",
            "helix_attn_device_info", "helix_status_string", "helix_attn_version")
 HELIX_OK = 0
 _lib = None
+
+
+class helix_strides(ctypes.Structure):
+    """Element strides (batch, head, row) of a logical [B, H, S, D] view; see the header."""
+    _fields_ = [("batch", ctypes.c_longlong), ("head", ctypes.c_longlong), ("row", ctypes.c_longlong)]
 
 
 class HelixLibraryError(RuntimeError):
@@ -39,6 +45,12 @@ def lib() -> ctypes.CDLL:
         vp, fp, i, f, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
         L.helix_attn_fwd.argtypes = [vp, vp, vp, vp, fp, i, i, i, i, f, i, vp]
         L.helix_attn_bwd.argtypes = [vp, vp, vp, vp, fp, vp, vp, vp, vp, vp, sz, i, i, i, i, f, i, vp]
+        sp = ctypes.POINTER(helix_strides)
+        L.helix_attn_fwd_strided.argtypes = [vp, sp, vp, sp, vp, sp, vp, sp, fp, i, i, i, i, f, i, vp]
+        L.helix_attn_bwd_strided.argtypes = [vp, sp, vp, sp, vp, sp, vp, sp, fp, vp, sp, vp, sp, vp, sp, vp, sp,
+                                             vp, sz, i, i, i, i, f, i, vp]
+        L.helix_attn_check_strides.argtypes = [sp, i, i, i, i]
+        L.helix_attn_check_strides.restype = i
         L.helix_attn_bwd_workspace_bytes.argtypes = [i, i, i, i]
         L.helix_attn_bwd_workspace_bytes.restype = sz
         L.helix_attn_bwd_preprocess.argtypes = [vp, vp, fp, i, i, i, i, vp]
@@ -50,7 +62,8 @@ def lib() -> ctypes.CDLL:
         L.helix_attn_version.argtypes = []
         L.helix_attn_device_info.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.helix_attn_device_info.restype = i
-        for name in ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head",
+        for name in ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_fwd_strided", "helix_attn_bwd_strided",
+                     "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head",
                      "helix_attn_bwd_dkdv",
                      "helix_attn_bwd_dq", "helix_attn_version"):
             getattr(L, name).restype = i
@@ -122,6 +135,45 @@ def helix_attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, workspace, scale, causal=Tru
     _raise(lib().helix_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO), _ptr(dq), _ptr(dk), _ptr(dv),
                                 _ptr(workspace), workspace.numel(), B, H, S, D, float(scale), int(causal),
                                 _stream(stream)), "helix_attn_bwd")
+
+
+def _view(name, t, shape):
+    """(pointer, strides) of a logical [B, H, S, D] bf16 view whose last dimension is contiguous."""
+    if t.dtype != torch.bfloat16 or not t.is_cuda or tuple(t.shape) != tuple(shape) or t.stride(3) != 1:
+        raise ValueError(f"{name}: need a CUDA bfloat16 view of shape {tuple(shape)} with unit stride in D")
+    sb, sh, ss, _ = t.stride()
+    return _ptr(t), ctypes.byref(helix_strides(sb, sh, ss))
+
+
+def helix_attn_check_strides(strides, B, H, S, D) -> int:
+    """Status for element strides (batch, head, row), or None for contiguous."""
+    arg = None if strides is None else ctypes.byref(helix_strides(*strides))
+    return int(lib().helix_attn_check_strides(arg, B, H, S, D))
+
+
+def helix_attn_fwd_strided(q, k, v, o, lse, scale, causal=True, stream=None):
+    """helix_attn_fwd on views: each of q, k, v, o has logical shape [B,H,S,D] and any strides the
+    library accepts (for example ``x.permute(1, 2, 0, 3)`` of an [S,B,H,D] activation)."""
+    B, H, S, D = q.shape
+    (pq, sq), (pk, sk), (pv, sv), (po, so) = (_view(n, t, (B, H, S, D)) for n, t in
+                                              (("q", q), ("k", k), ("v", v), ("o", o)))
+    _check_f32("lse", lse, (B, H, S))
+    _raise(lib().helix_attn_fwd_strided(pq, sq, pk, sk, pv, sv, po, so, _ptr(lse), B, H, S, D, float(scale),
+                                        int(causal), _stream(stream)), "helix_attn_fwd_strided")
+
+
+def helix_attn_bwd_strided(q, k, v, o, lse, dO, dq, dk, dv, workspace, scale, causal=True, stream=None):
+    """helix_attn_bwd on views (see helix_attn_fwd_strided)."""
+    B, H, S, D = q.shape
+    views = [_view(n, t, (B, H, S, D)) for n, t in (("q", q), ("k", k), ("v", v), ("o", o), ("dO", dO),
+                                                    ("dq", dq), ("dk", dk), ("dv", dv))]
+    _check_f32("lse", lse, (B, H, S))
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace: need a contiguous CUDA uint8 tensor")
+    (pq, sq), (pk, sk), (pv, sv), (po, so), (pg, sg), (pdq, sdq), (pdk, sdk), (pdv, sdv) = views
+    _raise(lib().helix_attn_bwd_strided(pq, sq, pk, sk, pv, sv, po, so, _ptr(lse), pg, sg, pdq, sdq, pdk, sdk,
+                                        pdv, sdv, _ptr(workspace), workspace.numel(), B, H, S, D, float(scale),
+                                        int(causal), _stream(stream)), "helix_attn_bwd_strided")
 
 
 def helix_attn_bwd_preprocess(o, dO, delta, stream=None):

@@ -9,7 +9,7 @@
 
 namespace {
 
-constexpr int kVersion = 100;  // 0.1.0
+constexpr int kVersion = 200;  // 0.2.0
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -20,7 +20,7 @@ int check_shape(int B, int H, int S, int D) {
   if (bh > 0x7fffffffLL / 8) return HELIX_ERR_BAD_SHAPE;          // workgroup ids stay in int
   if (S > (1 << 24)) return HELIX_ERR_BAD_SHAPE;                  // in-head offsets stay in 32 bits
   if ((double)bh * S * D >= 1099511627776.0) return HELIX_ERR_BAD_SHAPE;  // 2^40 elements
-  const long long tiles = (long long)((S + 63) / 64) * 8 * ((bh + 7) / 8);
+  const long long tiles = (long long)((S + 63) / 64 + 8) * 8 * bh;
   if (tiles > 0x7fffffffLL) return HELIX_ERR_BAD_SHAPE;           // grid size limit
   return HELIX_OK;
 }
@@ -42,6 +42,43 @@ int check_f32_ptrs(P... ptrs) {
   return HELIX_OK;
 }
 
+// Strides of a [B, H, S, D] view (NULL: contiguous).  Accepted: multiples of 8 elements, so
+// that every row starts on a 16-byte boundary, and "nested": ordered by stride, each
+// dimension steps over the whole extent of the next smaller one (rows over D), which holds
+// for any permutation of the dimensions of a dense or padded buffer and rules out overlap.
+int to_map(const helix_strides* st, int B, int H, int S, int D, helix::TensorMap* out) {
+  if (!st) { *out = helix::contiguous_map(H, S, D); return HELIX_OK; }
+  struct Dim { long long stride; long long extent; };
+  Dim d[3] = {{st->batch, B}, {st->head, H}, {st->row, S}};
+  for (const Dim& x : d) if (x.stride < 0 || (x.stride & 7)) return HELIX_ERR_BAD_STRIDE;
+  if (st->row < D || st->row > (1 << 24)) return HELIX_ERR_BAD_STRIDE;   // tile-relative byte offsets stay in 32 bits
+  for (int i = 0; i < 3; i++)
+    for (int j = i + 1; j < 3; j++)
+      if (d[j].stride < d[i].stride) { Dim t = d[i]; d[i] = d[j]; d[j] = t; }
+  long long span = D;   // elements covered by the dimensions handled so far
+  for (const Dim& x : d) {
+    if (x.extent == 1) continue;
+    if (x.stride < span) return HELIX_ERR_BAD_STRIDE;
+    if ((double)x.stride * (double)x.extent >= 1099511627776.0) return HELIX_ERR_BAD_STRIDE;   // 2^40 elements
+    span = x.stride * x.extent;
+  }
+  *out = helix::TensorMap{st->batch, st->head, (int)st->row};
+  return HELIX_OK;
+}
+
+helix::FwdMaps contiguous_fwd(int H, int S, int D) {
+  const helix::TensorMap m = helix::contiguous_map(H, S, D);
+  return helix::FwdMaps{m, m, m, m};
+}
+helix::BwdMaps contiguous_bwd(int H, int S, int D) {
+  const helix::TensorMap m = helix::contiguous_map(H, S, D);
+  return helix::BwdMaps{m, m, m, m, m, m, m, m};
+}
+
+int run_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
+            void* dq, void* dk, void* dv, float* delta, const helix::BwdMaps& maps,
+            int B, int H, int S, int D, float scale, int causal, hipStream_t st);
+
 int launched(hipError_t e) { return e == hipSuccess ? HELIX_OK : HELIX_ERR_LAUNCH; }
 
 #define HELIX_TRY(expr) do { int st_ = (expr); if (st_ != HELIX_OK) return st_; } while (0)
@@ -56,7 +93,28 @@ int helix_attn_fwd(const void* q, const void* k, const void* v, void* o, float* 
   HELIX_TRY(check_f32_ptrs((const void*)lse));
   HELIX_TRY(check_shape(B, H, S, D));
   HELIX_TRY(check_scale(scale));
-  return launched(helix::launch_fwd(q, k, v, o, lse, B * H, S, D, scale, causal != 0, (hipStream_t)stream));
+  return launched(helix::launch_fwd(q, k, v, o, lse, contiguous_fwd(H, S, D), B, H, S, D, scale, causal != 0, (hipStream_t)stream));
+}
+
+int helix_attn_check_strides(const helix_strides* strides, int B, int H, int S, int D) {
+  HELIX_TRY(check_shape(B, H, S, D));
+  helix::TensorMap m;
+  return to_map(strides, B, H, S, D, &m);
+}
+
+int helix_attn_fwd_strided(const void* q, const helix_strides* q_strides, const void* k, const helix_strides* k_strides,
+                           const void* v, const helix_strides* v_strides, void* o, const helix_strides* o_strides,
+                           float* lse, int B, int H, int S, int D, float scale, int causal, void* stream) {
+  HELIX_TRY(check_bf16_ptrs(q, k, v, (const void*)o));
+  HELIX_TRY(check_f32_ptrs((const void*)lse));
+  HELIX_TRY(check_shape(B, H, S, D));
+  HELIX_TRY(check_scale(scale));
+  helix::FwdMaps m;
+  HELIX_TRY(to_map(q_strides, B, H, S, D, &m.q));
+  HELIX_TRY(to_map(k_strides, B, H, S, D, &m.k));
+  HELIX_TRY(to_map(v_strides, B, H, S, D, &m.v));
+  HELIX_TRY(to_map(o_strides, B, H, S, D, &m.o));
+  return launched(helix::launch_fwd(q, k, v, o, lse, m, B, H, S, D, scale, causal != 0, (hipStream_t)stream));
 }
 
 size_t helix_attn_bwd_workspace_bytes(int B, int H, int S, int D) {
@@ -70,7 +128,7 @@ int helix_attn_bwd_preprocess(const void* o, const void* dO, float* delta,
   HELIX_TRY(check_bf16_ptrs(o, dO));
   HELIX_TRY(check_f32_ptrs((const void*)delta));
   HELIX_TRY(check_shape(B, H, S, D));
-  return launched(helix::launch_bwd_preprocess(o, dO, delta, B * H, S, D, (hipStream_t)stream));
+  return launched(helix::launch_bwd_preprocess(o, dO, delta, contiguous_bwd(H, S, D), B, H, S, D, (hipStream_t)stream));
 }
 
 int helix_attn_bwd_delta_head(const void* q, const void* k, const void* v, const void* dO,
@@ -81,7 +139,7 @@ int helix_attn_bwd_delta_head(const void* q, const void* k, const void* v, const
   HELIX_TRY(check_shape(B, H, S, D));
   HELIX_TRY(check_scale(scale));
   if (rows < 0) return HELIX_ERR_BAD_SHAPE;
-  return launched(helix::launch_bwd_delta_head(q, k, v, dO, lse, delta, B * H, S, D, rows, scale, causal != 0, (hipStream_t)stream));
+  return launched(helix::launch_bwd_delta_head(q, k, v, dO, lse, delta, contiguous_bwd(H, S, D), B, H, S, D, rows, scale, causal != 0, (hipStream_t)stream));
 }
 
 int helix_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* dO,
@@ -91,7 +149,7 @@ int helix_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void*
   HELIX_TRY(check_f32_ptrs((const void*)lse, (const void*)delta));
   HELIX_TRY(check_shape(B, H, S, D));
   HELIX_TRY(check_scale(scale));
-  return launched(helix::launch_bwd_dkdv(q, k, v, dO, lse, delta, dk, dv, B * H, S, D, scale, causal != 0, (hipStream_t)stream));
+  return launched(helix::launch_bwd_dkdv(q, k, v, dO, lse, delta, dk, dv, contiguous_bwd(H, S, D), B, H, S, D, scale, causal != 0, (hipStream_t)stream));
 }
 
 int helix_attn_bwd_dq(const void* q, const void* k, const void* v, const void* dO,
@@ -101,7 +159,7 @@ int helix_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d
   HELIX_TRY(check_f32_ptrs((const void*)lse, (const void*)delta));
   HELIX_TRY(check_shape(B, H, S, D));
   HELIX_TRY(check_scale(scale));
-  return launched(helix::launch_bwd_dq(q, k, v, dO, lse, delta, dq, B * H, S, D, scale, causal != 0, (hipStream_t)stream));
+  return launched(helix::launch_bwd_dq(q, k, v, dO, lse, delta, dq, contiguous_bwd(H, S, D), B, H, S, D, scale, causal != 0, (hipStream_t)stream));
 }
 
 int helix_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
@@ -115,13 +173,34 @@ int helix_attn_bwd(const void* q, const void* k, const void* v, const void* o, c
   if (!workspace) return HELIX_ERR_NULL_POINTER;
   if (!aligned(workspace, 256)) return HELIX_ERR_MISALIGNED;
   if (workspace_bytes < helix_attn_bwd_workspace_bytes(B, H, S, D)) return HELIX_ERR_WORKSPACE;
-  float* delta = static_cast<float*>(workspace);
-  hipStream_t st = (hipStream_t)stream;
-  const int BH = B * H;
-  HELIX_TRY(launched(helix::launch_bwd_preprocess(o, dO, delta, BH, S, D, st)));
-  if (causal) HELIX_TRY(launched(helix::launch_bwd_delta_head(q, k, v, dO, lse, delta, BH, S, D, HELIX_DELTA_HEAD_ROWS, scale, true, st)));
-  HELIX_TRY(launched(helix::launch_bwd_dkdv(q, k, v, dO, lse, delta, dk, dv, BH, S, D, scale, causal != 0, st)));
-  return launched(helix::launch_bwd_dq(q, k, v, dO, lse, delta, dq, BH, S, D, scale, causal != 0, st));
+  return run_bwd(q, k, v, o, lse, dO, dq, dk, dv, static_cast<float*>(workspace), contiguous_bwd(H, S, D),
+                 B, H, S, D, scale, causal, (hipStream_t)stream);
+}
+
+int helix_attn_bwd_strided(const void* q, const helix_strides* q_strides, const void* k, const helix_strides* k_strides,
+                           const void* v, const helix_strides* v_strides, const void* o, const helix_strides* o_strides,
+                           const float* lse, const void* dO, const helix_strides* dO_strides,
+                           void* dq, const helix_strides* dq_strides, void* dk, const helix_strides* dk_strides,
+                           void* dv, const helix_strides* dv_strides, void* workspace, size_t workspace_bytes,
+                           int B, int H, int S, int D, float scale, int causal, void* stream) {
+  HELIX_TRY(check_bf16_ptrs(q, k, v, o, dO, (const void*)dq, (const void*)dk, (const void*)dv));
+  HELIX_TRY(check_f32_ptrs((const void*)lse));
+  HELIX_TRY(check_shape(B, H, S, D));
+  HELIX_TRY(check_scale(scale));
+  if (!workspace) return HELIX_ERR_NULL_POINTER;
+  if (!aligned(workspace, 256)) return HELIX_ERR_MISALIGNED;
+  if (workspace_bytes < helix_attn_bwd_workspace_bytes(B, H, S, D)) return HELIX_ERR_WORKSPACE;
+  helix::BwdMaps m;
+  HELIX_TRY(to_map(q_strides, B, H, S, D, &m.q));
+  HELIX_TRY(to_map(k_strides, B, H, S, D, &m.k));
+  HELIX_TRY(to_map(v_strides, B, H, S, D, &m.v));
+  HELIX_TRY(to_map(o_strides, B, H, S, D, &m.o));
+  HELIX_TRY(to_map(dO_strides, B, H, S, D, &m.dO));
+  HELIX_TRY(to_map(dq_strides, B, H, S, D, &m.dq));
+  HELIX_TRY(to_map(dk_strides, B, H, S, D, &m.dk));
+  HELIX_TRY(to_map(dv_strides, B, H, S, D, &m.dv));
+  return run_bwd(q, k, v, o, lse, dO, dq, dk, dv, static_cast<float*>(workspace), m, B, H, S, D, scale, causal,
+                 (hipStream_t)stream);
 }
 
 int helix_attn_device_info(int* compute_units, int* clock_khz) {
@@ -144,6 +223,7 @@ const char* helix_status_string(int status) {
     case HELIX_ERR_BAD_SCALE: return "bad scale: must be finite and > 0";
     case HELIX_ERR_WORKSPACE: return "workspace too small";
     case HELIX_ERR_LAUNCH: return "kernel launch failed";
+    case HELIX_ERR_BAD_STRIDE: return "bad strides: multiples of 8 elements, row stride in [D, 2^24], dimensions nested without overlap";
     default: return "unknown status";
   }
 }
@@ -151,3 +231,17 @@ const char* helix_status_string(int status) {
 int helix_attn_version(void) { return kVersion; }
 
 }  // extern "C"
+
+namespace {
+
+// The whole backward: delta, its refinement on the first rows (causal only), dK/dV, dQ.
+int run_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
+            void* dq, void* dk, void* dv, float* delta, const helix::BwdMaps& maps,
+            int B, int H, int S, int D, float scale, int causal, hipStream_t st) {
+  HELIX_TRY(launched(helix::launch_bwd_preprocess(o, dO, delta, maps, B, H, S, D, st)));
+  if (causal) HELIX_TRY(launched(helix::launch_bwd_delta_head(q, k, v, dO, lse, delta, maps, B, H, S, D, HELIX_DELTA_HEAD_ROWS, scale, true, st)));
+  HELIX_TRY(launched(helix::launch_bwd_dkdv(q, k, v, dO, lse, delta, dk, dv, maps, B, H, S, D, scale, causal != 0, st)));
+  return launched(helix::launch_bwd_dq(q, k, v, dO, lse, delta, dq, maps, B, H, S, D, scale, causal != 0, st));
+}
+
+}  // namespace

@@ -167,7 +167,8 @@ template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
                 const __bf16* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ delta,
-                __bf16* __restrict__ dk, __bf16* __restrict__ dv, int BH, int S, int T, float scale) {
+                __bf16* __restrict__ dk, __bf16* __restrict__ dv, BwdMaps maps, int BH, int H, int S, int T,
+                float scale) {
   using G = Geometry<D>;
   constexpr int BN = 128, BM = 64, KS = G::KS, DB = G::DB;
   extern __shared__ __align__(16) char smem[];
@@ -180,9 +181,10 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
   const int n0 = tc.tile * BN;
   const int wave_kmin = n0 + 32 * w;
   const int my_key = wave_kmin + n;
-  const size_t head_off = (size_t)tc.bh * S * D;
-  const __bf16* qh = q + head_off;
-  const __bf16* gh = dO + head_off;
+  const __bf16* qh = q + head_offset(maps.q, tc.bh, H);
+  const __bf16* gh = dO + head_offset(maps.dO, tc.bh, H);
+  const __bf16* kh = k + head_offset(maps.k, tc.bh, H);
+  const __bf16* vh = v + head_offset(maps.v, tc.bh, H);
   const float* lse_h = lse + (size_t)tc.bh * S;
   const float* delta_h = delta + (size_t)tc.bh * S;
   const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, scale * kLog2e)));
@@ -194,8 +196,8 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
     const int row = my_key < S ? my_key : S - 1;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
-      kf[ks] = *reinterpret_cast<const bf16x8*>(k + head_off + (size_t)row * D + 16 * ks + 8 * half);
-      vf[ks] = *reinterpret_cast<const bf16x8*>(v + head_off + (size_t)row * D + 16 * ks + 8 * half);
+      kf[ks] = *reinterpret_cast<const bf16x8*>(kh + (size_t)row * maps.k.row + 16 * ks + 8 * half);
+      vf[ks] = *reinterpret_cast<const bf16x8*>(vh + (size_t)row * maps.v.row + 16 * ks + 8 * half);
     }
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) { pin(kf[ks]); pin(vf[ks]); }
@@ -214,14 +216,14 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
   int t_hi = ((S - m_start) % BM != 0) ? nt - 1 : nt;
   if (t_hi < t_lo) t_hi = t_lo;
 
-  const TileLoader<D, BM, 4> loader(lane, w);
+  const TileLoader<D, BM, 4> qload(lane, w, maps.q.row), gload(lane, w, maps.dO.row);
   constexpr int NDMA = 2 * TileLoader<D, BM, 4>::N + 2;      // copy instructions per wave and tile
   int t = 0, st = 0;                                          // tile and its stage (t % 4)
   auto copy_tile = [&](int tt, int stage) {
     const uint32_t sb = base + stage * G::STAGE;
     const int row0 = m_start + tt * BM;
-    loader.issue(qh, row0, S, sb);
-    loader.issue(gh, row0, S, sb + G::TILE);
+    qload.issue(qh, row0, S, sb);
+    gload.issue(gh, row0, S, sb + G::TILE);
     int r = row0 + lane;
     r = r < S ? r : S - 1;
     dma_dword(lse_h, (uint32_t)r * 4, sb + G::STATS + w * 512);
@@ -343,8 +345,8 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
   for (; t < nt; t++) { copy_ahead(); plain_tile(); finish_tile(); }
 
   if (my_key < S) {
-    __bf16* dkrow = dk + head_off + (size_t)my_key * D;
-    __bf16* dvrow = dv + head_off + (size_t)my_key * D;
+    __bf16* dkrow = dk + head_offset(maps.dk, tc.bh, H) + (size_t)my_key * maps.dk.row;
+    __bf16* dvrow = dv + head_offset(maps.dv, tc.bh, H) + (size_t)my_key * maps.dv.row;
 #pragma unroll
     for (int db = 0; db < DB; db++)
 #pragma unroll
@@ -360,27 +362,27 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
 
 template <int D, bool CAUSAL>
 static hipError_t launch_dkdv_t(const void* q, const void* k, const void* v, const void* dO,
-                                const float* lse, const float* delta, void* dk, void* dv,
-                                int BH, int S, float scale, hipStream_t stream) {
+                                const float* lse, const float* delta, void* dk, void* dv, const BwdMaps& maps,
+                                int B, int H, int S, float scale, hipStream_t stream) {
   constexpr int BN = 128;
-  const int T = (S + BN - 1) / BN;
-  const int grid = 8 * ((BH + 7) / 8) * T;
+  const int T = (S + BN - 1) / BN, BH = B * H;
+  const unsigned grid = (unsigned)grid_blocks(BH, T);
   const size_t lds = Geometry<D>::NSTAGE * Geometry<D>::STAGE;
   auto kern = bwd_dkdv_kernel<D, CAUSAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v,
-                     (const __bf16*)dO, lse, delta, (__bf16*)dk, (__bf16*)dv, BH, S, T, scale);
+                     (const __bf16*)dO, lse, delta, (__bf16*)dk, (__bf16*)dv, maps, BH, H, S, T, scale);
   return hipGetLastError();
 }
 
 hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* dO,
-                           const float* lse, const float* delta, void* dk, void* dv,
-                           int BH, int S, int D, float scale, bool causal, hipStream_t stream) {
-  if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, dO, lse, delta, dk, dv, BH, S, scale, stream)
-                              : launch_dkdv_t<128, false>(q, k, v, dO, lse, delta, dk, dv, BH, S, scale, stream);
-  return causal ? launch_dkdv_t<64, true>(q, k, v, dO, lse, delta, dk, dv, BH, S, scale, stream)
-                : launch_dkdv_t<64, false>(q, k, v, dO, lse, delta, dk, dv, BH, S, scale, stream);
+                           const float* lse, const float* delta, void* dk, void* dv, const BwdMaps& maps,
+                           int B, int H, int S, int D, float scale, bool causal, hipStream_t stream) {
+  if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, dO, lse, delta, dk, dv, maps, B, H, S, scale, stream)
+                              : launch_dkdv_t<128, false>(q, k, v, dO, lse, delta, dk, dv, maps, B, H, S, scale, stream);
+  return causal ? launch_dkdv_t<64, true>(q, k, v, dO, lse, delta, dk, dv, maps, B, H, S, scale, stream)
+                : launch_dkdv_t<64, false>(q, k, v, dO, lse, delta, dk, dv, maps, B, H, S, scale, stream);
 }
 
 }  // namespace helix

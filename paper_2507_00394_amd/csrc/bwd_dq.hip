@@ -117,7 +117,7 @@ template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(512, 1)
 bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
                    const __bf16* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ delta,
-                   __bf16* __restrict__ dq, int BH, int S, int T, float scale) {
+                   __bf16* __restrict__ dq, BwdMaps maps, int BH, int H, int S, int T, float scale) {
   constexpr int BM = 256, BN = 64;
   constexpr int KS = D / 16, DB = D / 32;
   constexpr int TILE = BN * D * 2, HALF = 32 * D * 2;
@@ -131,9 +131,10 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
   const int half = lane >> 5, n = lane & 31;
   const int q0 = tc.tile * BM;
   const int my_q = q0 + 32 * w + n;
-  const size_t head_off = (size_t)tc.bh * S * D;
-  const __bf16* kh = k + head_off;
-  const __bf16* vh = v + head_off;
+  const __bf16* qh = q + head_offset(maps.q, tc.bh, H);
+  const __bf16* gh = dO + head_offset(maps.dO, tc.bh, H);
+  const __bf16* kh = k + head_offset(maps.k, tc.bh, H);
+  const __bf16* vh = v + head_offset(maps.v, tc.bh, H);
   const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, scale * kLog2e)));
   const uint32_t base = lds_base(smem);
 
@@ -143,8 +144,8 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
     const int row = my_q < S ? my_q : S - 1;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
-      qf[ks] = *reinterpret_cast<const bf16x8*>(q + head_off + (size_t)row * D + 16 * ks + 8 * half);
-      gf[ks] = *reinterpret_cast<const bf16x8*>(dO + head_off + (size_t)row * D + 16 * ks + 8 * half);
+      qf[ks] = *reinterpret_cast<const bf16x8*>(qh + (size_t)row * maps.q.row + 16 * ks + 8 * half);
+      gf[ks] = *reinterpret_cast<const bf16x8*>(gh + (size_t)row * maps.dO.row + 16 * ks + 8 * half);
     }
     lse2 = lse[(size_t)tc.bh * S + row] * kLog2e;
     dl = delta[(size_t)tc.bh * S + row];
@@ -167,12 +168,12 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
   else if (CAUSAL) { n_w = (wave_qmax < S ? wave_qmax : S - 1) / BN + 1; n_full = (wave_qmin + 1) / BN; }
   else { n_w = n_tiles; n_full = S / BN; }
 
-  const TileLoader<D, BN, 8> loader(lane, w);
+  const TileLoader<D, BN, 8> kload(lane, w, maps.k.row), vload(lane, w, maps.v.row);
   constexpr int NDMA = 2 * TileLoader<D, BN, 8>::N;
   int j = 0, st = 0;   // tile and its stage (j % 4)
   auto copy_tile = [&](int jj, int stage) {
-    loader.issue(kh, jj * BN, S, base + stage * STAGE);
-    loader.issue(vh, jj * BN, S, base + stage * STAGE + TILE);
+    kload.issue(kh, jj * BN, S, base + stage * STAGE);
+    vload.issue(vh, jj * BN, S, base + stage * STAGE + TILE);
   };
   auto copy_ahead = [&]() {
     if (j + 3 < n_tiles) copy_tile(j + 3, (st + 3) & 3);   // replaces tile j-1
@@ -276,7 +277,7 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
   }
 
   if (my_q < S) {
-    __bf16* row = dq + head_off + (size_t)my_q * D;
+    __bf16* row = dq + head_offset(maps.dq, tc.bh, H) + (size_t)my_q * maps.dq.row;
 #pragma unroll
     for (int db = 0; db < DB; db++)
 #pragma unroll
@@ -291,27 +292,27 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
 
 template <int D, bool CAUSAL>
 static hipError_t launch_dq_pipe_t(const void* q, const void* k, const void* v, const void* dO,
-                                   const float* lse, const float* delta, void* dq,
-                                   int BH, int S, float scale, hipStream_t stream) {
+                                   const float* lse, const float* delta, void* dq, const BwdMaps& maps,
+                                   int B, int H, int S, float scale, hipStream_t stream) {
   constexpr int BM = 256, BN = 64;
-  const int T = (S + BM - 1) / BM;
-  const int grid = 8 * ((BH + 7) / 8) * T;
+  const int T = (S + BM - 1) / BM, BH = B * H;
+  const unsigned grid = (unsigned)grid_blocks(BH, T);
   const size_t lds = 4 * 2 * BN * D * 2;
   auto kern = bwd_dq_pipe_kernel<D, CAUSAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, stream, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v,
-                     (const __bf16*)dO, lse, delta, (__bf16*)dq, BH, S, T, scale);
+                     (const __bf16*)dO, lse, delta, (__bf16*)dq, maps, BH, H, S, T, scale);
   return hipGetLastError();
 }
 
 hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void* dO,
-                         const float* lse, const float* delta, void* dq,
-                         int BH, int S, int D, float scale, bool causal, hipStream_t stream) {
-  if (D == 128) return causal ? launch_dq_pipe_t<128, true>(q, k, v, dO, lse, delta, dq, BH, S, scale, stream)
-                              : launch_dq_pipe_t<128, false>(q, k, v, dO, lse, delta, dq, BH, S, scale, stream);
-  return causal ? launch_dq_pipe_t<64, true>(q, k, v, dO, lse, delta, dq, BH, S, scale, stream)
-                : launch_dq_pipe_t<64, false>(q, k, v, dO, lse, delta, dq, BH, S, scale, stream);
+                         const float* lse, const float* delta, void* dq, const BwdMaps& maps,
+                         int B, int H, int S, int D, float scale, bool causal, hipStream_t stream) {
+  if (D == 128) return causal ? launch_dq_pipe_t<128, true>(q, k, v, dO, lse, delta, dq, maps, B, H, S, scale, stream)
+                              : launch_dq_pipe_t<128, false>(q, k, v, dO, lse, delta, dq, maps, B, H, S, scale, stream);
+  return causal ? launch_dq_pipe_t<64, true>(q, k, v, dO, lse, delta, dq, maps, B, H, S, scale, stream)
+                : launch_dq_pipe_t<64, false>(q, k, v, dO, lse, delta, dq, maps, B, H, S, scale, stream);
 }
 
 }  // namespace helix

@@ -18,8 +18,10 @@
 //                                              | their row sum, bf16 packs | LDS: V operand i
 //     slots 8..15  MFMA O^T += V(h)^T P(h)^T   | VALU row maximum of S(h+1) | LDS: K operand i of S(h+2)
 // followed by the (rare) rescale of the accumulators when a row maximum outgrew its
-// reference.  K and V tiles are copied global -> LDS asynchronously one tile ahead into two
-// buffers each; one workgroup barrier per 64-key tile.  The last tile of every wave (the only
+// reference.  K and V tiles are copied global -> LDS asynchronously three tiles ahead into four
+// buffers each (a step already reads the first operands of the tile after its own, so two
+// tiles are in use, one is landing and one is being issued); one workgroup barrier per
+// 64-key tile.  The last tile of every wave (the only
 // one the causal mask cuts, or the ragged end of the sequence) runs unpipelined.
 #include "helix_common.hpp"
 #include "kernels.hpp"
@@ -189,14 +191,14 @@ __device__ __forceinline__ float half_step(const f32x16& s_cur, f32x16& s_next,
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(512, 1)
 fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
-           __bf16* __restrict__ o, float* __restrict__ lse, int BH, int S, int T, float scale) {
+           __bf16* __restrict__ o, float* __restrict__ lse, FwdMaps maps, int BH, int H, int S, int T, float scale) {
   constexpr int BM = 256, BN = 64;
   constexpr int KS = D / 16;   // contraction steps of Q K^T
   constexpr int DB = D / 32;   // 32-wide blocks of the head dimension
   constexpr int TILE = BN * D * 2;
   constexpr int HALF = 32 * D * 2;   // bytes of 32 key rows
   constexpr int VREGION = 4 * TILE;
-  extern __shared__ __align__(16) char smem[];   // K[4] then V[3]; K tile j in buffer j % 4, V tile j in j % 3
+  extern __shared__ __align__(16) char smem[];   // K[4] then V[4]; tile j in buffer j % 4
 
   const TileCoord tc = map_block(blockIdx.x, BH, T, true);
   if (!tc.valid) return;
@@ -205,10 +207,9 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   const int half = lane >> 5, n = lane & 31;
   const int q0 = tc.tile * BM;
   const int my_q = q0 + 32 * w + n;
-  const size_t head_off = (size_t)tc.bh * S * D;
-  const __bf16* qh = q + head_off;
-  const __bf16* kh = k + head_off;
-  const __bf16* vh = v + head_off;
+  const __bf16* qh = q + head_offset(maps.q, tc.bh, H);
+  const __bf16* kh = k + head_offset(maps.k, tc.bh, H);
+  const __bf16* vh = v + head_offset(maps.v, tc.bh, H);
   const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, scale * kLog2e)));
   const uint32_t base = lds_base(smem);
 
@@ -217,7 +218,7 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
     const int row = my_q < S ? my_q : S - 1;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++)
-      qf[ks] = *reinterpret_cast<const bf16x8*>(qh + (size_t)row * D + 16 * ks + 8 * half);
+      qf[ks] = *reinterpret_cast<const bf16x8*>(qh + (size_t)row * maps.q.row + 16 * ks + 8 * half);
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) pin(qf[ks]);
   }
@@ -239,11 +240,11 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   else if (CAUSAL) { n_w = (wave_qmax < S ? wave_qmax : S - 1) / BN + 1; n_full = (wave_qmin + 1) / BN; }
   else { n_w = n_tiles; n_full = S / BN; }
 
-  const TileLoader<D, BN, 8> loader(lane, w);
-  loader.issue(kh, 0, S, base);
-  loader.issue(vh, 0, S, base + VREGION);
-  if (n_tiles > 1) { loader.issue(kh, BN, S, base + TILE); loader.issue(vh, BN, S, base + VREGION + TILE); }
-  if (n_tiles > 2) loader.issue(kh, 2 * BN, S, base + 2 * TILE);
+  const TileLoader<D, BN, 8> kload(lane, w, maps.k.row), vload(lane, w, maps.v.row);
+  kload.issue(kh, 0, S, base);
+  vload.issue(vh, 0, S, base + VREGION);
+  if (n_tiles > 1) { kload.issue(kh, BN, S, base + TILE); vload.issue(vh, BN, S, base + VREGION + TILE); }
+  if (n_tiles > 2) { kload.issue(kh, 2 * BN, S, base + 2 * TILE); vload.issue(vh, 2 * BN, S, base + VREGION + 2 * TILE); }
   wait_tile_loads();
   __syncthreads();
 
@@ -274,29 +275,32 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   // The tile sweep is split per wave into the pipelined tiles 0 .. n_w-2 and a second loop
   // with the wave's last tile (plain path) and the tiles it only helps to copy.  Every wave
   // of the workgroup runs n_tiles iterations in total and meets the others at the barriers.
-  int rk = 0, rv = 0;   // j % 4, j % 3
+  int rk = 0;   // j % 4
   int j = 0;
   auto copy_ahead = [&]() {
-    // copies run two tiles ahead: K(j+3) replaces K(j-1) (last read in the first half of
-    // iteration j-1), V(j+2) replaces V(j-1)
-    if (j + 3 < n_tiles) loader.issue(kh, (j + 3) * BN, S, base + ((rk + 3) & 3) * TILE);
-    if (j + 2 < n_tiles) loader.issue(vh, (j + 2) * BN, S, base + VREGION + (rv == 0 ? 2 : rv - 1) * TILE);
+    // copies run three tiles ahead: K(j+3), V(j+3) replace K(j-1), V(j-1), last read in
+    // iteration j-1.  Iteration j itself reads tile j and, ahead of its use, the first
+    // operands of tile j+1 (K in both halves, V at the end of the second), so tiles up to j+1
+    // must be complete when it starts.
+    if (j + 3 < n_tiles) {
+      kload.issue(kh, (j + 3) * BN, S, base + ((rk + 3) & 3) * TILE);
+      vload.issue(vh, (j + 3) * BN, S, base + VREGION + ((rk + 3) & 3) * TILE);
+    }
   };
   auto finish_tile = [&]() {
-    // K(j+2) and V(j+1), issued one iteration ago, must have landed; this iteration's copies
+    // K(j+2) and V(j+2), issued one iteration ago, must have landed; this iteration's copies
     // (2 + 2 instructions per wave) may stay in flight.
     if (j + 3 < n_tiles) wait_tile_loads_except<2 * TileLoader<D, BN, 8>::N>();
     else wait_tile_loads();
     __syncthreads();
     rk = (rk + 1) & 3;
-    rv = (rv == 2) ? 0 : rv + 1;
   };
 
   for (; j < n_w - 1; j++) {
     copy_ahead();
     const int khi_step = (rk == 3) ? -3 * TILE : TILE;   // K buffer of tile j   -> j+1
     const int klo_step = (rk == 2) ? -3 * TILE : TILE;   // K buffer of tile j+1 -> j+2
-    const int v_step = (rv == 2) ? -2 * TILE : TILE;     // V buffer of tile j   -> j+1
+    const int v_step = khi_step;                         // V buffer of tile j   -> j+1
     // half a: score S_b(j) | P_a(j) | O += V_a(j) P_a(j) | read K_b(j) 4..7, K_a(j+1) 0..3
     const float mb = half_step<D, HALF, 0, 0, false>(sa, sb, kop, vop, qf, klo, khi, vaddr, v_step, oacc, c, st);
     check_reference<DB>(mb, c, st, oacc);
@@ -346,7 +350,7 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   const float ltot = half_sum(st.lsum[0] + st.lsum[1]);
   const float inv = 1.f / ltot;
   if (my_q < S) {
-    __bf16* orow = o + head_off + (size_t)my_q * D;
+    __bf16* orow = o + head_offset(maps.o, tc.bh, H) + (size_t)my_q * maps.o.row;
 #pragma unroll
     for (int db = 0; db < DB; db++)
 #pragma unroll
@@ -362,25 +366,25 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
 
 template <int D, bool CAUSAL>
 static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, void* o, float* lse,
-                               int BH, int S, float scale, hipStream_t stream) {
+                               const FwdMaps& maps, int B, int H, int S, float scale, hipStream_t stream) {
   constexpr int BM = 256, BN = 64;
-  const int T = (S + BM - 1) / BM;
-  const int grid = 8 * ((BH + 7) / 8) * T;
-  const size_t lds = 7 * BN * D * 2;
+  const int T = (S + BM - 1) / BM, BH = B * H;
+  const unsigned grid = (unsigned)grid_blocks(BH, T);
+  const size_t lds = 8 * BN * D * 2;
   auto kern = fwd_kernel<D, CAUSAL>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, stream, (const __bf16*)q, (const __bf16*)k,
-                     (const __bf16*)v, (__bf16*)o, lse, BH, S, T, scale);
+                     (const __bf16*)v, (__bf16*)o, lse, maps, BH, H, S, T, scale);
   return hipGetLastError();
 }
 
-hipError_t launch_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
-                      int BH, int S, int D, float scale, bool causal, hipStream_t stream) {
-  if (D == 128) return causal ? launch_fwd_t<128, true>(q, k, v, o, lse, BH, S, scale, stream)
-                              : launch_fwd_t<128, false>(q, k, v, o, lse, BH, S, scale, stream);
-  return causal ? launch_fwd_t<64, true>(q, k, v, o, lse, BH, S, scale, stream)
-                : launch_fwd_t<64, false>(q, k, v, o, lse, BH, S, scale, stream);
+hipError_t launch_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const FwdMaps& maps,
+                      int B, int H, int S, int D, float scale, bool causal, hipStream_t stream) {
+  if (D == 128) return causal ? launch_fwd_t<128, true>(q, k, v, o, lse, maps, B, H, S, scale, stream)
+                              : launch_fwd_t<128, false>(q, k, v, o, lse, maps, B, H, S, scale, stream);
+  return causal ? launch_fwd_t<64, true>(q, k, v, o, lse, maps, B, H, S, scale, stream)
+                : launch_fwd_t<64, false>(q, k, v, o, lse, maps, B, H, S, scale, stream);
 }
 
 }  // namespace helix

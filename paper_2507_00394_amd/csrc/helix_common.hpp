@@ -3,6 +3,7 @@
 // transposing LDS read and the cross-half lane exchange.
 #pragma once
 #include <hip/hip_runtime.h>
+#include "kernels.hpp"
 #include <stdint.h>
 
 namespace helix {
@@ -68,12 +69,12 @@ struct TileStage {
   static constexpr int CH = D / 8;                 // 16-byte chunks per row
   static constexpr int N = (ROWS * CH + NT - 1) / NT;
   u32x4 r[N];
-  __device__ __forceinline__ void fetch(const __bf16* head_base, int row0, int nrows, int tid) {
+  __device__ __forceinline__ void fetch(const __bf16* head_base, int row_stride, int row0, int nrows, int tid) {
 #pragma unroll
     for (int i = 0; i < N; i++) {
       int id = tid + NT * i;
       int row = id / CH, c = id % CH;
-      if (ROWS * CH % NT == 0 || id < ROWS * CH) r[i] = load_chunk(head_base, row0 + row, nrows, D, c * 8);
+      if (ROWS * CH % NT == 0 || id < ROWS * CH) r[i] = load_chunk(head_base, row0 + row, nrows, row_stride, c * 8);
     }
   }
   __device__ __forceinline__ void commit(char* lds, int tid) const {
@@ -114,18 +115,22 @@ struct TileLoader {
   static constexpr int N = (KB + NWAVES - 1) / NWAVES;    // pieces per wave
   static_assert(KB % NWAVES == 0, "every wave copies the same number of pieces");
   int wave, lane_row;  // lane_row: this lane's row inside a piece
-  uint32_t off[N];     // byte offset inside the tile of the chunk this lane fetches for piece i:
-                       // row * 2D + 16 * (logical chunk)
-  __device__ __forceinline__ TileLoader(int lane, int wave_) : wave(wave_), lane_row(lane / CH) {
+  uint32_t row_bytes;  // distance between consecutive rows of the tensor in global memory
+  uint32_t off[N];     // byte offset from the tile's first row of the chunk this lane fetches for
+                       // piece i: row * row_bytes + 16 * (logical chunk)
+  // row_stride: elements between consecutive rows of the tensor (D when the head is contiguous).
+  __device__ __forceinline__ TileLoader(int lane, int wave_, int row_stride)
+      : wave(wave_), lane_row(lane / CH), row_bytes((uint32_t)row_stride * 2u) {
 #pragma unroll
     for (int i = 0; i < N; i++) {
       const int r = (wave + NWAVES * i) * ROWS_PER_KB + lane_row;
-      off[i] = r * (D * 2) + (((lane % CH) ^ swizzle<D>(r)) << 4);
+      off[i] = r * row_bytes + (((lane % CH) ^ swizzle<D>(r)) << 4);
     }
   }
   // lds_tile_addr: 32-bit LDS address of the destination tile (wave-uniform).
   __device__ __forceinline__ void issue(const __bf16* head_base, int row0, int nrows, uint32_t lds_tile_addr) const {
-    const __bf16* tile_base = uniform_ptr(head_base + (size_t)row0 * D);
+    const __bf16* tile_base = uniform_ptr(reinterpret_cast<const __bf16*>(
+        reinterpret_cast<const char*>(head_base) + (size_t)row0 * row_bytes));
     const int last = __builtin_amdgcn_readfirstlane(nrows - 1 - row0);   // last valid tile row (>= ROWS-1 unless ragged)
     if (last >= ROWS - 1) {
 #pragma unroll
@@ -140,7 +145,7 @@ struct TileLoader {
         const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile_addr + (wave + NWAVES * i) * 1024);
         const int row = (wave + NWAVES * i) * ROWS_PER_KB + lane_row;
         const int rr = row < last ? row : last;
-        const uint32_t o = off[i] - (uint32_t)(row - rr) * (D * 2);
+        const uint32_t o = off[i] - (uint32_t)(row - rr) * row_bytes;
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                      :: "v"(o), "s"(tile_base), "s"(dst) : "memory");
       }
@@ -221,18 +226,36 @@ __device__ __forceinline__ bf16x8 pack_half(const f32x16& acc, int t) {
   return __builtin_convertvector(x, bf16x8);
 }
 
-// Map a linear workgroup id to (batch*head slice, tile) so that the 8 XCDs (workgroup id
-// mod 8 selects the XCD) each sweep whole heads, heaviest tiles first; `heavy_last` tiles
-// are those with the highest index (forward, dQ) or the lowest (dK/dV).
+// Map a linear workgroup id to (batch*head slice, tile).  Workgroup id mod 8 selects the XCD, and
+// each XCD sweeps whole "virtual heads", heaviest tiles first (`heavy_is_high`: the heaviest
+// tiles are those with the highest index (forward, dQ), else the lowest (dK/dV)).  A virtual
+// head is one of P interleaved parts of a head (tiles congruent mod P), with P the smallest
+// power of two that makes BH * P a multiple of 8: with 32 heads a virtual head is a head, with
+// the 4 or 5 heads of one GPU's share of a tensor-parallel layer (Section 2.2) a head is
+// spread over 2 or 8 XCDs so that none of them idles.
 struct TileCoord { int bh; int tile; bool valid; };
+__host__ __device__ inline int head_parts(int BH) { return (BH & 1) ? 8 : (BH & 2) ? 4 : (BH & 4) ? 2 : 1; }
+// Number of workgroups to launch for BH slices of T tiles.
+__host__ __device__ inline long long grid_blocks(int BH, int T) {
+  const int P = head_parts(BH);
+  return (long long)BH * P * ((T + P - 1) / P);
+}
 __device__ __forceinline__ TileCoord map_block(int n, int BH, int T, bool heavy_is_high) {
   TileCoord c;
-  int xcd = n & 7, s = n >> 3;
-  c.bh = xcd + 8 * (s / T);
-  int t = s % T;
-  c.tile = heavy_is_high ? (T - 1 - t) : t;
-  c.valid = c.bh < BH;
+  const int P = head_parts(BH), TP = (T + P - 1) / P;
+  const int xcd = n & 7, s = n >> 3;
+  const int vh = xcd + 8 * (s / TP);
+  const int k = (s % TP) * P + (vh & (P - 1));   // rank of the tile inside its head, heaviest first
+  c.bh = vh / P;
+  c.tile = heavy_is_high ? (T - 1 - k) : k;
+  c.valid = c.bh < BH && k < T;
   return c;
+}
+
+// Element offset of row 0 of slice bh = b * H + h.
+__device__ __forceinline__ size_t head_offset(const TensorMap& m, int bh, int H) {
+  const int b = bh / H;
+  return (size_t)((long long)b * m.batch + (long long)(bh - b * H) * m.head);
 }
 
 }  // namespace helix

@@ -1,23 +1,36 @@
-// Host-side launchers of the gfx950 attention kernels.  Shapes are validated by the
-// C-ABI layer before any of these is called; BH = B*H.
+// Host-side launchers of the gfx950 attention kernels.  Shapes, strides and alignment are
+// validated by the C-ABI layer before any of these is called.
 #pragma once
 #include <hip/hip_runtime.h>
 
 namespace helix {
 
-hipError_t launch_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
-                      int BH, int S, int D, float scale, bool causal, hipStream_t stream);
-hipError_t launch_bwd_preprocess(const void* o, const void* dO, float* delta,
-                                 int BH, int S, int D, hipStream_t stream);
+// Where a [B, H, S, D] tensor lives: element strides of batch, head and row; the D elements
+// of a row are contiguous.
+struct TensorMap {
+  long long batch, head;
+  int row;
+};
+inline TensorMap contiguous_map(int H, int S, int D) {
+  return TensorMap{(long long)H * S * D, (long long)S * D, D};
+}
+struct FwdMaps { TensorMap q, k, v, o; };
+struct BwdMaps { TensorMap q, k, v, o, dO, dq, dk, dv; };
+
+// lse, delta and every other per-row fp32 array are contiguous [B, H, S].
+hipError_t launch_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const FwdMaps& maps,
+                      int B, int H, int S, int D, float scale, bool causal, hipStream_t stream);
+hipError_t launch_bwd_preprocess(const void* o, const void* dO, float* delta, const BwdMaps& maps,
+                                 int B, int H, int S, int D, hipStream_t stream);
 // delta_i = sum_j p_ij dp_ij for query rows 0..rows-1 of every head, overwriting delta there.
 hipError_t launch_bwd_delta_head(const void* q, const void* k, const void* v, const void* dO,
-                                 const float* lse, float* delta, int BH, int S, int D, int rows,
-                                 float scale, bool causal, hipStream_t stream);
+                                 const float* lse, float* delta, const BwdMaps& maps, int B, int H, int S, int D,
+                                 int rows, float scale, bool causal, hipStream_t stream);
 hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* dO,
-                           const float* lse, const float* delta, void* dk, void* dv,
-                           int BH, int S, int D, float scale, bool causal, hipStream_t stream);
+                           const float* lse, const float* delta, void* dk, void* dv, const BwdMaps& maps,
+                           int B, int H, int S, int D, float scale, bool causal, hipStream_t stream);
 hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void* dO,
-                         const float* lse, const float* delta, void* dq,
-                         int BH, int S, int D, float scale, bool causal, hipStream_t stream);
+                         const float* lse, const float* delta, void* dq, const BwdMaps& maps,
+                         int B, int H, int S, int D, float scale, bool causal, hipStream_t stream);
 
 }  // namespace helix

@@ -23,9 +23,10 @@ def run_fwd_bwd(bits, scale, causal=True, fused_bwd=True):
     """bits: dict q,k,v,dO of uint16 [B,H,S,D].  Returns dict of device tensors."""
     q, k, v, g = (to_dev(bits[t]) for t in ("q", "k", "v", "dO"))
     B, H, S, D = q.shape
-    o = torch.empty_like(q); lse = torch.empty((B, H, S), dtype=torch.float32, device="cuda")
+    nan = float("nan")   # outputs start as NaN so that anything the kernels leave unwritten fails the checks
+    o = torch.full_like(q, nan); lse = torch.full((B, H, S), nan, dtype=torch.float32, device="cuda")
     hx.helix_attn_fwd(q, k, v, o, lse, scale, causal)
-    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    dq, dk, dv = torch.full_like(q, nan), torch.full_like(q, nan), torch.full_like(q, nan)
     if fused_bwd:
         ws = torch.empty(hx.helix_attn_bwd_workspace_bytes(B, H, S, D), dtype=torch.uint8, device="cuda")
         hx.helix_attn_bwd(q, k, v, o, lse, g, dq, dk, dv, ws, scale, causal)

@@ -35,8 +35,8 @@ def test_every_declared_symbol_is_exported(L):
 
 def test_version_and_status_strings(L):
     assert L.helix_attn_version() >= 100
-    seen = {hx.status_string(s) for s in range(8)}
-    assert len(seen) == 8 and hx.status_string(0) == "ok" and hx.status_string(99) == "unknown status"
+    seen = {hx.status_string(s) for s in range(9)}
+    assert len(seen) == 9 and hx.status_string(0) == "ok" and hx.status_string(99) == "unknown status"
 
 
 def test_workspace_bytes(L):
@@ -68,6 +68,48 @@ def test_validation_precedes_any_device_work(L):
     assert L.helix_attn_bwd_delta_head(p, p, p, p, p, p, -1, 1, 1, 8, 64, 0.1, 1, None) == 2
     assert L.helix_attn_bwd_dkdv(p, p, p, p, p, p, p, odd, 1, 1, 8, 64, 0.1, 1, None) == 4
     assert L.helix_attn_bwd_dq(p, p, p, p, p, p, p, 1, 1, 8, 128, -0.1, 1, None) == 5
+
+
+def test_stride_validation(L):
+    """Strided entry points: the stride rules of the header, checked on the host."""
+    p = ctypes.c_void_p(0x10000)
+    B, H, S, D = 2, 4, 96, 64
+    st = lambda b, h, r: ctypes.byref(hx.helix_strides(b, h, r))
+    good = {
+        "contiguous": st(H * S * D, S * D, D),
+        "seq_major": st(H * D, D, B * H * D),                  # [S, B, H, D] viewed as [B, H, S, D]
+        "fused_qkv": st(3 * H * D, D, B * 3 * H * D),          # a third of an [S, B, 3*H*D] buffer
+        "interleaved_qkv": st(H * 3 * D, 3 * D, B * H * 3 * D),  # [S, B, H, 3*D]
+        "padded_rows": st(H * S * (D + 8), S * (D + 8), D + 8),
+    }
+    def fwd(sq=None, so=None, **kw):
+        return L.helix_attn_fwd_strided(kw.get("q", p), sq, p, None, p, None, p, so, p, B, H, S, kw.get("D", D), 0.1, 1, None)
+    bad = {
+        "row_below_D": st(H * S * D, S * D, D - 8),
+        "not_multiple_of_8": st(H * S * D + 4, S * D, D),
+        "negative": st(-H * S * D, S * D, D),
+        "heads_overlap_rows": st(H * S * D, D, D),             # head stride inside the span of the rows
+        "batch_overlaps": st(S * D, S * D, D),                  # batch and head strides coincide
+        "row_too_large": st(0, 0, (1 << 24) + 8),
+    }
+    for name, s_ in bad.items():
+        assert fwd(sq=s_) == 8, name
+        assert fwd(so=s_) == 8, name
+    assert fwd(sq=bad["row_below_D"], q=None) == 1              # pointer checks come first
+    assert fwd(sq=bad["row_below_D"], D=96) == 3                # then the shape
+    for name, s_ in good.items():
+        assert L.helix_attn_check_strides(s_, B, H, S, D) == 0, name
+    for name, s_ in bad.items():
+        assert L.helix_attn_check_strides(s_, B, H, S, D) == 8, name
+    assert L.helix_attn_check_strides(None, B, H, S, D) == 0
+    assert L.helix_attn_check_strides(None, B, H, S, 80) == 3
+    # extent-1 dimensions may carry any (aligned) stride, as torch views of size 1 do
+    assert hx.helix_attn_check_strides((0, 64, 128), 1, 2, 96, 64) == 0
+    assert hx.helix_attn_check_strides((8, 8, 64), 1, 1, 96, 64) == 0
+    bwd = lambda s_, ws=1 << 20: L.helix_attn_bwd_strided(p, None, p, None, p, None, p, None, p, p, None, p, None, p, s_,
+                                                         p, None, p, ws, B, H, S, D, 0.1, 1, None)
+    assert bwd(bad["heads_overlap_rows"]) == 8 and bwd(bad["negative"]) == 8
+    assert bwd(good["seq_major"], ws=16) == 6                   # workspace size is checked before the strides
 
 
 def test_binding_refuses_cpu_tensors(L):
