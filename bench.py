@@ -34,6 +34,13 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="workload id 1..5 (default 4: the metric's workload)")
+    ap.add_argument("--share-heads", type=int, default=0,
+                    help="instead of a numbered workload: one GPU's share of the heads under 8-way sequence/tensor "
+                         "parallelism (Section 2.2; Table 3: 2 heads for 1.3B, 4 for 3B and 7B, 5 for a 13B-like layer), "
+                         "through the strided entry points on sequence-major buffers")
+    ap.add_argument("--seq", type=int, default=131072, help="sequence length of the --share-heads workload")
+    ap.add_argument("--layout", choices=("fused_qkv", "contiguous"), default="fused_qkv",
+                    help="--share-heads: q,k,v views of one [S,B,3,H,D] buffer and [S,B,H,D] activations, or [B,H,S,D]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=49152)
     return ap.parse_args()
@@ -60,6 +67,61 @@ def cpu_baseline(cfg, sample_tokens):
                       f"of the workload, {dt:.1f} s"}
 
 
+def share_bench(args):
+    """One GPU's share of a layer (few heads, full sequence) on strided views; whole calls only."""
+    import torch
+
+    from paper_2507_00394_amd import binding as hx
+
+    B, H, S, D = 1, args.share_heads, args.seq, 128
+    scale = D ** -0.5
+    n_cu, clock_khz = hx.helix_attn_device_info()
+    peak_tflops = n_cu * PEAK_FLOP_PER_CLK_PER_CU * clock_khz / 1e9
+    gen = torch.Generator(device="cuda").manual_seed(250700394)
+    rnd = lambda *shape: torch.randn(*shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    if args.layout == "fused_qkv":
+        qkv, dqkv = rnd(S, B, 3, H, D), torch.empty(S, B, 3, H, D, device="cuda", dtype=torch.bfloat16)
+        q, k, v = (qkv[:, :, i].permute(1, 2, 0, 3) for i in range(3))
+        dq, dk, dv = (dqkv[:, :, i].permute(1, 2, 0, 3) for i in range(3))
+        g = rnd(S, B, H, D).permute(1, 2, 0, 3)
+        o = torch.empty(S, B, H, D, device="cuda", dtype=torch.bfloat16).permute(1, 2, 0, 3)
+    else:
+        q, k, v, g = (rnd(B, H, S, D) for _ in range(4))
+        o, dq, dk, dv = (torch.empty_like(q) for _ in range(4))
+    lse = torch.empty(B, H, S, device="cuda", dtype=torch.float32)
+    ws = torch.empty(hx.helix_attn_bwd_workspace_bytes(B, H, S, D), dtype=torch.uint8, device="cuda")
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        hx.helix_attn_fwd_strided(q, k, v, o, lse, scale, True)
+        if ev: ev[1].record()
+        hx.helix_attn_bwd_strided(q, k, v, o, lse, g, dq, dk, dv, ws, scale, True)
+        if ev: ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    unit = S * (S + 1) // 2 * B * H * D
+    ms_fwd = float(np.mean([e[0].elapsed_time(e[1]) for e in evs])); ms_bwd = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    value = 14 * unit / (wall / args.steps) / 1e12
+    print(json.dumps({
+        "metric": "causal attn fwd+bwd TFLOP/s, one GPU's share of the heads at 8-way sequence parallelism; % of bf16 MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"per-GPU share: causal MHA fwd+bwd, B={B} H={H} S={S} D={D}, layout {args.layout}, "
+                               f"bf16 iid N(0,1), scale=1/sqrt({D})", "B": B, "H": H, "S": S, "D": D, "layout": args.layout},
+        "pct_of_bf16_mfma_peak": 100 * value / peak_tflops, "peak_tflops_denominator": peak_tflops,
+        "fwd_ms": ms_fwd, "bwd_ms": ms_bwd, "fwd_tflops": 4 * unit / ms_fwd / 1e9, "bwd_tflops": 10 * unit / ms_bwd / 1e9,
+        "roofline": None, "cpu_baseline": None}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -71,9 +133,11 @@ def main():
     from paper_2507_00394_amd import binding as hx
     from paper_2507_00394_amd import inputs as I
 
-    cfg = I.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.share_heads:
+        return share_bench(args)
+    cfg = I.CONFIGS[args.config]
     n_cu, clock_khz = hx.helix_attn_device_info()
     clock_ghz = clock_khz / 1e6
     peak_tflops = n_cu * PEAK_FLOP_PER_CLK_PER_CU * clock_ghz / 1e3
