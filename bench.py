@@ -41,6 +41,16 @@ def parse():
     ap.add_argument("--seq", type=int, default=131072, help="sequence length of the --share-heads workload")
     ap.add_argument("--layout", choices=("fused_qkv", "contiguous"), default="fused_qkv",
                     help="--share-heads: q,k,v views of one [S,B,3,H,D] buffer and [S,B,H,D] activations, or [B,H,S,D]")
+    ap.add_argument("--overlap", choices=("none", "copy", "cu-mask"), default="none",
+                    help="robustness of the path to a concurrent transfer (Section 4.3 hides stage-to-stage transfers "
+                         "behind attention; Section 5.3 argues they take few compute units): 'copy' runs device-to-device "
+                         "copies on a second stream during the timed steps, 'cu-mask' runs the steps on a stream that "
+                         "may use only 256 - N compute units")
+    ap.add_argument("--copy-mib", type=int, default=256, help="--overlap copy: size of one copy (256 MiB = one GPU's "
+                    "share of the 2*b*s*h bytes a 7B layer boundary moves at 128k tokens, 8-way sequence parallel)")
+    ap.add_argument("--copy-gbs", type=float, default=0.0, help="--overlap copy: pace the copies to about this many GB/s "
+                    "(0: back to back, as fast as the device copies)")
+    ap.add_argument("--masked-cus", type=int, default=16, help="--overlap cu-mask: compute units withheld from the path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=49152)
     return ap.parse_args()
@@ -122,6 +132,81 @@ def share_bench(args):
         "roofline": None, "cpu_baseline": None}))
 
 
+def cu_masked_stream(n_cu, masked):
+    """A torch stream on which kernels may use all but `masked` compute units.  The withheld
+    units are mask bits 33*i mod n_cu, which spreads them over the XCDs whether consecutive
+    bits go round the XCDs or fill one XCD after the other."""
+    import ctypes
+
+    import torch
+
+    hip = ctypes.CDLL("libamdhip64.so")
+    words = (n_cu + 31) // 32
+    bits = [1] * n_cu
+    for i in range(masked):
+        bits[(33 * i) % n_cu] = 0
+    mask = (ctypes.c_uint32 * words)(*[sum(bits[32 * w + b] << b for b in range(32) if 32 * w + b < n_cu) for w in range(words)])
+    stream = ctypes.c_void_p()
+    err = hip.hipExtStreamCreateWithCUMask(ctypes.byref(stream), ctypes.c_uint32(words), mask)
+    if err != 0:
+        raise RuntimeError(f"hipExtStreamCreateWithCUMask failed with {err}")
+    return torch.cuda.ExternalStream(stream.value)
+
+
+def overlap_bench(args, step, flops_per_step):
+    """Times `step` alone, then under the chosen disturbance; prints one JSON line."""
+    import torch
+
+    def timed(n, stream=None, during=None):
+        ctx = torch.cuda.stream(stream) if stream is not None else torch.cuda.stream(torch.cuda.current_stream())
+        with ctx:
+            for _ in range(2):
+                step()
+            torch.cuda.synchronize()
+            done = torch.cuda.Event()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                step()
+            done.record()
+            extra = during(done) if during else None
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / n, extra
+
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    base, _ = timed(args.steps)
+    info = {"mode": args.overlap}
+    if args.overlap == "copy":
+        side = torch.cuda.Stream()
+        n = args.copy_mib << 20
+        src = torch.empty(n, dtype=torch.uint8, device="cuda"); dst = torch.empty_like(src)
+        def during(done):
+            copies, t0 = 0, time.perf_counter()
+            with torch.cuda.stream(side):
+                while not done.query():
+                    if args.copy_gbs > 0:
+                        ahead = copies * n / (args.copy_gbs * 1e9) - (time.perf_counter() - t0)
+                        if ahead > 0:
+                            time.sleep(min(ahead, 0.005)); continue
+                    elif copies % 64 == 63:
+                        side.synchronize()          # keep the queue short: at most 64 copies ahead
+                    dst.copy_(src, non_blocking=True); copies += 1
+                side.synchronize()
+            return copies, time.perf_counter() - t0
+        t, (copies, dt) = timed(args.steps, during=during)
+        info.update({"copy_mib": args.copy_mib, "copies": copies, "copy_gbs_each_way": copies * n / dt / 1e9,
+                     "paced_to_gbs": args.copy_gbs or None})
+    else:
+        t, _ = timed(args.steps, stream=cu_masked_stream(n_cu, args.masked_cus))
+        info.update({"masked_cus": args.masked_cus, "cus": n_cu,
+                     "slowdown_if_proportional": n_cu / (n_cu - args.masked_cus)})
+    info.update({"ms_alone": base * 1e3, "ms_disturbed": t * 1e3, "slowdown": t / base})
+    print(json.dumps({"metric": "causal attn fwd+bwd TFLOP/s under a concurrent disturbance", "value": flops_per_step / t / 1e12,
+                      "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": 2, "ms_per_step": t * 1e3,
+                      "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "as the default run, disturbed"}, "alone_tflops": flops_per_step / base / 1e12,
+                      "overlap": info, "roofline": None, "cpu_baseline": None}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -164,6 +249,8 @@ def main():
         mark(4); hx.helix_attn_bwd_dq(q, k, v, g, lse, delta, dq, cfg.scale, cfg.causal)
         mark(5)
 
+    if args.overlap != "none":
+        return overlap_bench(args, step, 14 * cfg.pairs_per_head * B * H * D)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
