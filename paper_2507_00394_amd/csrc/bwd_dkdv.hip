@@ -219,7 +219,7 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
   const TileLoader<D, BM, 4> qload(lane, w, maps.q.row), gload(lane, w, maps.dO.row);
   constexpr int NDMA = 2 * TileLoader<D, BM, 4>::N + 2;      // copy instructions per wave and tile
   int t = 0, st = 0;                                          // tile and its stage (t % 4)
-  auto copy_tile = [&](int tt, int stage) {
+  auto copy_tile = [&](int tt, int stage) __attribute__((always_inline)) {
     const uint32_t sb = base + stage * G::STAGE;
     const int row0 = m_start + tt * BM;
     qload.issue(qh, row0, S, sb);
@@ -229,10 +229,10 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
     dma_dword(lse_h, (uint32_t)r * 4, sb + G::STATS + w * 512);
     dma_dword(delta_h, (uint32_t)r * 4, sb + G::STATS + w * 512 + 256);
   };
-  auto copy_ahead = [&]() {
+  auto copy_ahead = [&]() __attribute__((always_inline)) {
     if (t + 3 < nt) copy_tile(t + 3, (st + 3) & 3);   // replaces tile t-1
   };
-  auto finish_tile = [&]() {
+  auto finish_tile = [&]() __attribute__((always_inline)) {
     // tiles up to t+2 must have landed before the next iteration starts (it reads t+1 and
     // t+2); the copy of tile t+3 issued in this iteration may stay in flight
     if (t + 3 < nt) wait_tile_loads_except<NDMA>();
@@ -247,7 +247,7 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
   __syncthreads();
 
   // One 32-row block through the plain path: everything in program order, masks applied.
-  auto plain_block = [&](int blk) {
+  auto plain_block = [&](int blk) __attribute__((always_inline)) {
     const int r0 = m_start + t * BM + 32 * blk;   // global row of the block's first query
     const char* qt = smem + st * G::STAGE;
     const char* gt = qt + G::TILE;
@@ -286,7 +286,7 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
       }
     }
   };
-  auto plain_tile = [&]() {
+  auto plain_tile = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int blk = 0; blk < 2; blk++) {
       const int r0 = m_start + t * BM + 32 * blk;

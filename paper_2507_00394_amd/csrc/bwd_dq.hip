@@ -171,14 +171,14 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
   const TileLoader<D, BN, 8> kload(lane, w, maps.k.row), vload(lane, w, maps.v.row);
   constexpr int NDMA = 2 * TileLoader<D, BN, 8>::N;
   int j = 0, st = 0;   // tile and its stage (j % 4)
-  auto copy_tile = [&](int jj, int stage) {
+  auto copy_tile = [&](int jj, int stage) __attribute__((always_inline)) {
     kload.issue(kh, jj * BN, S, base + stage * STAGE);
     vload.issue(vh, jj * BN, S, base + stage * STAGE + TILE);
   };
-  auto copy_ahead = [&]() {
+  auto copy_ahead = [&]() __attribute__((always_inline)) {
     if (j + 3 < n_tiles) copy_tile(j + 3, (st + 3) & 3);   // replaces tile j-1
   };
-  auto finish_tile = [&]() {
+  auto finish_tile = [&]() __attribute__((always_inline)) {
     // tiles up to j+2 have landed before the next iteration (which reads j+1 and j+2) starts
     if (j + 3 < n_tiles) wait_tile_loads_except<NDMA>();
     else wait_tile_loads();

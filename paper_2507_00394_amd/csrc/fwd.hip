@@ -277,7 +277,7 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   // of the workgroup runs n_tiles iterations in total and meets the others at the barriers.
   int rk = 0;   // j % 4
   int j = 0;
-  auto copy_ahead = [&]() {
+  auto copy_ahead = [&]() __attribute__((always_inline)) {
     // copies run three tiles ahead: K(j+3), V(j+3) replace K(j-1), V(j-1), last read in
     // iteration j-1.  Iteration j itself reads tile j and, ahead of its use, the first
     // operands of tile j+1 (K in both halves, V at the end of the second), so tiles up to j+1
@@ -287,7 +287,7 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
       vload.issue(vh, (j + 3) * BN, S, base + VREGION + ((rk + 3) & 3) * TILE);
     }
   };
-  auto finish_tile = [&]() {
+  auto finish_tile = [&]() __attribute__((always_inline)) {
     // K(j+2) and V(j+2), issued one iteration ago, must have landed; this iteration's copies
     // (2 + 2 instructions per wave) may stay in flight.
     if (j + 3 < n_tiles) wait_tile_loads_except<2 * TileLoader<D, BN, 8>::N>();
