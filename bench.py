@@ -51,6 +51,10 @@ def parse():
     ap.add_argument("--copy-gbs", type=float, default=0.0, help="--overlap copy: pace the copies to about this many GB/s "
                     "(0: back to back, as fast as the device copies)")
     ap.add_argument("--masked-cus", type=int, default=16, help="--overlap cu-mask: compute units withheld from the path")
+    ap.add_argument("--qkv-linear", action="store_true",
+                    help="time the QKV linear layer of the attention stage (Section 4.2) instead of attention: "
+                         "M = --seq tokens, K = --hidden, N = 3 * --share-heads * 128 columns (default 4 heads)")
+    ap.add_argument("--hidden", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=49152)
     return ap.parse_args()
@@ -207,6 +211,64 @@ def overlap_bench(args, step, flops_per_step):
                       "overlap": info, "roofline": None, "cpu_baseline": None}))
 
 
+def linear_bench(args):
+    """The QKV linear layer: forward and backward (input and weight gradients), one GPU's columns."""
+    import torch
+
+    from paper_2507_00394_amd import binding as hx
+    from paper_2507_00394_amd import inputs as I
+
+    H = args.share_heads or 4
+    M, K, N = args.seq, args.hidden, 3 * H * 128
+    n_cu, clock_khz = hx.helix_attn_device_info()
+    peak_tflops = n_cu * PEAK_FLOP_PER_CLK_PER_CU * clock_khz / 1e9
+    gen = torch.Generator(device="cuda").manual_seed(250700394)
+    rnd = lambda r, c, std=1.0: (torch.randn(r, c, generator=gen, device="cuda", dtype=torch.float32) * std).to(torch.bfloat16)
+    a, w, g = rnd(M, K), rnd(K, N, 0.02), rnd(M, N)
+    qkv, da = torch.empty(M, N, device="cuda", dtype=torch.bfloat16), torch.empty(M, K, device="cuda", dtype=torch.bfloat16)
+    dw = torch.empty(K, N, device="cuda", dtype=torch.float32)
+    ws = torch.empty(max(hx.helix_qkv_linear_bwd_workspace_bytes(M, K, N), 1), dtype=torch.uint8, device="cuda")
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        hx.helix_qkv_linear_fwd(a, w, qkv)
+        if ev: ev[1].record()
+        hx.helix_qkv_linear_bwd(a, w, g, da, dw, ws)
+        if ev: ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    flops = 2 * M * K * N
+    ms_fwd = float(np.mean([e[0].elapsed_time(e[1]) for e in evs])); ms_bwd = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    value = 3 * flops / (wall / args.steps) / 1e12
+    out = {"metric": "QKV linear layer fwd+bwd TFLOP/s (Table 1: 6bsh^2 per product, one GPU's columns); % of bf16 MFMA peak",
+           "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"qkv[M,N] = a[M,K] w[K,N] and both backward products, M={M} K={K} N={N}, a, dqkv ~ N(0,1), "
+                                  f"w ~ N(0, 0.02^2), bf16", "M": M, "K": K, "N": N},
+           "pct_of_bf16_mfma_peak": 100 * value / peak_tflops, "fwd_ms": ms_fwd, "bwd_ms": ms_bwd,
+           "fwd_tflops": flops / ms_fwd / 1e9, "bwd_tflops": 2 * flops / ms_bwd / 1e9,
+           "roofline": {"bound": "mfma", "kernel": "gemm (forward)", "achieved": flops / ms_fwd / 1e9, "peak": 2500.0,
+                        "unit": "TFLOP/s", "frac": flops / ms_fwd / 1e9 / 2500.0, "traffic": None,
+                        "flops_per_launch": flops, "avg_launch_ms": ms_fwd}}
+    if not args.no_cpu_baseline:
+        from oracle import linear_ref as L
+        rows = min(M, 65536)
+        af, wf, gf = (t.float().cpu().numpy().astype(np.float64) for t in (a[:rows], w, g[:rows]))
+        t0 = time.perf_counter(); L.linear_fwd_ref(af, wf); L.linear_bwd_ref(af, wf, gf); dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 3 * 2 * rows * K * N / dt / 1e12, "unit": "TFLOP/s", "cores": len(os.sched_getaffinity(0)),
+                               "kind": "oracle", "sample": f"oracle.linear_ref forward + backward (fp64) on the first {rows} rows, {dt:.1f} s"}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -220,6 +282,8 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.qkv_linear:
+        return linear_bench(args)
     if args.share_heads:
         return share_bench(args)
     cfg = I.CONFIGS[args.config]

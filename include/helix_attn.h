@@ -147,6 +147,35 @@ int helix_attn_bwd_strided(const void* q, const helix_strides* q_strides,
                            void* workspace, size_t workspace_bytes,
                            int B, int H, int S, int D, float scale, int causal, void* stream);
 
+/* The QKV linear layer on the attention stage.  HelixPipe sends the layer's input A and its
+ * weights to the stage that runs attention instead of Q, K, V (Section 4.2, 2bsh + 3h^2
+ * instead of 4bsh elements), so the product runs right before the attention kernels and, with
+ * N = 3*H*D columns, writes the [S, B, 3, H, D] buffer that helix_attn_fwd_strided reads in
+ * place (Table 1, "QKV Linear": 6bsh^2 FLOPs forward, as much for each backward product).
+ *   forward : qkv[M][N] = a[M][K] * w[K][N]                      bf16 in, fp32 accumulate, bf16 out
+ *   backward: da[M][K]  = dqkv[M][N] * w[K][N]^T                 bf16 out
+ *             dw[K][N]  = a[M][K]^T * dqkv[M][N]                 fp32 out (overwritten, not accumulated)
+ * M = S*B rows (tokens), K = hidden size, N = this GPU's share of the 3h output columns.
+ * All matrices are row-major device memory, 16-byte aligned; ld* is the number of elements
+ * between consecutive rows (>= the row length, a multiple of 8, at most 2^23).  K and N must be
+ * multiples of 128; M is arbitrary for the forward and a multiple of 32 for the backward
+ * (HELIX_ERR_BAD_SHAPE otherwise; HELIX_ERR_BAD_STRIDE for a bad ld).  No bias (Table 1 neglects it).
+ * The backward cuts the weight gradient's contraction over the M tokens into parts that run side
+ * by side and are then summed in a fixed order (bit-reproducible, no atomics); the parts live in
+ * `workspace`: device memory of at least helix_qkv_linear_bwd_workspace_bytes(M, K, N) bytes,
+ * 256-byte aligned, owned by the caller, contents undefined afterwards; it may be NULL when that
+ * size is 0 (HELIX_ERR_NULL_POINTER / _MISALIGNED / _WORKSPACE otherwise).
+ * Asynchronous on `stream`; nothing is allocated; inputs are not written. */
+int helix_qkv_linear_fwd(const void* a, long long lda, const void* w, long long ldw,
+                         void* qkv, long long ldqkv, int M, int K, int N, void* stream);
+int helix_qkv_linear_bwd(const void* a, long long lda, const void* w, long long ldw,
+                         const void* dqkv, long long lddqkv, void* da, long long ldda,
+                         float* dw, long long lddw, void* workspace, size_t workspace_bytes,
+                         int M, int K, int N, void* stream);
+/* Bytes of scratch helix_qkv_linear_bwd needs (0 for an invalid shape or when no split is used).
+ * Pure host arithmetic. */
+size_t helix_qkv_linear_bwd_workspace_bytes(int M, int K, int N);
+
 /* Whether `strides` (NULL: contiguous) is acceptable for a [B, H, S, D] view: HELIX_OK,
  * HELIX_ERR_BAD_STRIDE, or the shape errors of the other calls.  Pure host arithmetic: the
  * same check the *_strided entry points apply to each of their tensors. */

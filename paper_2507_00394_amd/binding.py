@@ -14,7 +14,8 @@ import torch
 
 LIB_PATH = pathlib.Path(__file__).resolve().parent / "csrc" / "libhelix_attn.so"
 EXPORTS = ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_fwd_strided", "helix_attn_bwd_strided",
-           "helix_attn_check_strides", "helix_attn_bwd_workspace_bytes",
+           "helix_attn_check_strides", "helix_qkv_linear_fwd", "helix_qkv_linear_bwd", "helix_qkv_linear_bwd_workspace_bytes",
+           "helix_attn_bwd_workspace_bytes",
            "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head", "helix_attn_bwd_dkdv", "helix_attn_bwd_dq",
            "helix_attn_device_info", "helix_status_string", "helix_attn_version")
 HELIX_OK = 0
@@ -51,6 +52,13 @@ def lib() -> ctypes.CDLL:
                                              vp, sz, i, i, i, i, f, i, vp]
         L.helix_attn_check_strides.argtypes = [sp, i, i, i, i]
         L.helix_attn_check_strides.restype = i
+        ll = ctypes.c_longlong
+        L.helix_qkv_linear_fwd.argtypes = [vp, ll, vp, ll, vp, ll, i, i, i, vp]
+        L.helix_qkv_linear_bwd.argtypes = [vp, ll, vp, ll, vp, ll, vp, ll, fp, ll, vp, sz, i, i, i, vp]
+        L.helix_qkv_linear_bwd_workspace_bytes.argtypes = [i, i, i]
+        L.helix_qkv_linear_bwd_workspace_bytes.restype = sz
+        L.helix_qkv_linear_fwd.restype = i
+        L.helix_qkv_linear_bwd.restype = i
         L.helix_attn_bwd_workspace_bytes.argtypes = [i, i, i, i]
         L.helix_attn_bwd_workspace_bytes.restype = sz
         L.helix_attn_bwd_preprocess.argtypes = [vp, vp, fp, i, i, i, i, vp]
@@ -212,3 +220,36 @@ def helix_attn_bwd_dq(q, k, v, dO, lse, delta, dq, scale, causal=True, stream=No
     _check_f32("lse", lse, (B, H, S)); _check_f32("delta", delta, (B, H, S))
     _raise(lib().helix_attn_bwd_dq(_ptr(q), _ptr(k), _ptr(v), _ptr(dO), _ptr(lse), _ptr(delta), _ptr(dq),
                                    B, H, S, D, float(scale), int(causal), _stream(stream)), "helix_attn_bwd_dq")
+
+
+def _matrix(name, t, rows, cols, dtype=torch.bfloat16):
+    """(pointer, leading dimension) of a 2-D device matrix whose rows are contiguous."""
+    if t.dtype != dtype or not t.is_cuda or tuple(t.shape) != (rows, cols) or t.stride(1) != 1:
+        raise ValueError(f"{name}: need a CUDA {dtype} matrix of shape ({rows}, {cols}) with contiguous rows")
+    return _ptr(t), t.stride(0)
+
+
+def helix_qkv_linear_fwd(a, w, qkv, stream=None):
+    """qkv[M,N] <- a[M,K] @ w[K,N]; 2-D views with contiguous rows (qkv may be the [S*B, 3*H*D] view of a fused buffer)."""
+    M, K = a.shape
+    N = w.shape[1]
+    (pa, lda), (pw, ldw), (pq, ldq) = _matrix("a", a, M, K), _matrix("w", w, K, N), _matrix("qkv", qkv, M, N)
+    _raise(lib().helix_qkv_linear_fwd(pa, lda, pw, ldw, pq, ldq, M, K, N, _stream(stream)), "helix_qkv_linear_fwd")
+
+
+def helix_qkv_linear_bwd_workspace_bytes(M, K, N) -> int:
+    return int(lib().helix_qkv_linear_bwd_workspace_bytes(M, K, N))
+
+
+def helix_qkv_linear_bwd(a, w, dqkv, da, dw, workspace=None, stream=None):
+    """da[M,K] <- dqkv @ w^T (bf16), dw[K,N] <- a^T @ dqkv (fp32); workspace: uint8 CUDA tensor of
+    helix_qkv_linear_bwd_workspace_bytes(M, K, N) bytes (None if that is 0)."""
+    M, K = a.shape
+    N = w.shape[1]
+    (pa, lda), (pw, ldw), (pg, ldg) = _matrix("a", a, M, K), _matrix("w", w, K, N), _matrix("dqkv", dqkv, M, N)
+    (pda, ldda), (pdw, lddw) = _matrix("da", da, M, K), _matrix("dw", dw, K, N, torch.float32)
+    if workspace is not None and (workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous()):
+        raise ValueError("workspace: need a contiguous CUDA uint8 tensor")
+    _raise(lib().helix_qkv_linear_bwd(pa, lda, pw, ldw, pg, ldg, pda, ldda, pdw, lddw, _ptr(workspace),
+                                      0 if workspace is None else workspace.numel(), M, K, N, _stream(stream)),
+           "helix_qkv_linear_bwd")

@@ -6,6 +6,8 @@
 
 #include <cmath>
 #include <cstdint>
+#include <initializer_list>
+#include <utility>
 
 namespace {
 
@@ -78,6 +80,16 @@ helix::BwdMaps contiguous_bwd(int H, int S, int D) {
 int run_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
             void* dq, void* dk, void* dv, float* delta, const helix::BwdMaps& maps,
             int B, int H, int S, int D, float scale, int causal, hipStream_t st);
+
+// Shapes and leading dimensions of the linear layer; `need_m32`: the product contracts over M.
+int check_linear(int M, int K, int N, bool need_m32, std::initializer_list<std::pair<long long, int>> lds) {
+  if (M < 1 || K < 1 || N < 1) return HELIX_ERR_BAD_SHAPE;
+  if ((K & 127) || (N & 127) || (need_m32 && (M & 31))) return HELIX_ERR_BAD_SHAPE;
+  if (K > (1 << 20) || N > (1 << 20) || (long long)((M + 255) / 256 + 8) * ((N > K ? N : K) / 128) > 0x7fffffffLL / 8) return HELIX_ERR_BAD_SHAPE;
+  for (const auto& ld : lds)
+    if (ld.first < ld.second || (ld.first & 7) || ld.first > (1 << 23)) return HELIX_ERR_BAD_STRIDE;
+  return HELIX_OK;
+}
 
 int launched(hipError_t e) { return e == hipSuccess ? HELIX_OK : HELIX_ERR_LAUNCH; }
 
@@ -203,6 +215,34 @@ int helix_attn_bwd_strided(const void* q, const helix_strides* q_strides, const 
                  (hipStream_t)stream);
 }
 
+int helix_qkv_linear_fwd(const void* a, long long lda, const void* w, long long ldw, void* qkv, long long ldqkv,
+                         int M, int K, int N, void* stream) {
+  HELIX_TRY(check_bf16_ptrs(a, w, (const void*)qkv));
+  HELIX_TRY(check_linear(M, K, N, false, {{lda, K}, {ldw, N}, {ldqkv, N}}));
+  return launched(helix::launch_linear_fwd(a, lda, w, ldw, qkv, ldqkv, M, K, N, (hipStream_t)stream));
+}
+
+size_t helix_qkv_linear_bwd_workspace_bytes(int M, int K, int N) {
+  if (check_linear(M, K, N, true, {}) != HELIX_OK) return 0;
+  return (helix::linear_bwd_workspace_bytes(M, K, N) + 255) & ~(size_t)255;
+}
+
+int helix_qkv_linear_bwd(const void* a, long long lda, const void* w, long long ldw, const void* dqkv, long long lddqkv,
+                         void* da, long long ldda, float* dw, long long lddw, void* workspace, size_t workspace_bytes,
+                         int M, int K, int N, void* stream) {
+  HELIX_TRY(check_bf16_ptrs(a, w, dqkv, (const void*)da, (const void*)dw));
+  HELIX_TRY(check_linear(M, K, N, true, {{lda, K}, {ldw, N}, {lddqkv, N}, {ldda, K}, {lddw, N}}));
+  const size_t need = helix_qkv_linear_bwd_workspace_bytes(M, K, N);
+  if (need > 0) {
+    if (!workspace) return HELIX_ERR_NULL_POINTER;
+    if (!aligned(workspace, 256)) return HELIX_ERR_MISALIGNED;
+    if (workspace_bytes < need) return HELIX_ERR_WORKSPACE;
+  }
+  HELIX_TRY(launched(helix::launch_linear_bwd_input(dqkv, lddqkv, w, ldw, da, ldda, M, K, N, (hipStream_t)stream)));
+  return launched(helix::launch_linear_bwd_weight(a, lda, dqkv, lddqkv, dw, lddw, static_cast<float*>(workspace), M, K, N,
+                                                  (hipStream_t)stream));
+}
+
 int helix_attn_device_info(int* compute_units, int* clock_khz) {
   if (!compute_units || !clock_khz) return HELIX_ERR_NULL_POINTER;
   int dev = 0;
@@ -217,13 +257,13 @@ const char* helix_status_string(int status) {
   switch (status) {
     case HELIX_OK: return "ok";
     case HELIX_ERR_NULL_POINTER: return "null pointer argument";
-    case HELIX_ERR_BAD_SHAPE: return "bad shape: B, H, S must be >= 1 and within the index limits";
+    case HELIX_ERR_BAD_SHAPE: return "bad shape: extents must be >= 1, within the index limits and, for the linear layer, multiples of the tile sizes";
     case HELIX_ERR_UNSUPPORTED_HEAD_DIM: return "unsupported head dimension: D must be 64 or 128";
     case HELIX_ERR_MISALIGNED: return "misaligned pointer: bf16 tensors need 16 bytes, fp32 4, workspace 256";
     case HELIX_ERR_BAD_SCALE: return "bad scale: must be finite and > 0";
     case HELIX_ERR_WORKSPACE: return "workspace too small";
     case HELIX_ERR_LAUNCH: return "kernel launch failed";
-    case HELIX_ERR_BAD_STRIDE: return "bad strides: multiples of 8 elements, row stride in [D, 2^24], dimensions nested without overlap";
+    case HELIX_ERR_BAD_STRIDE: return "bad strides: multiples of 8 elements, row stride at least the row length and within the index limits, dimensions nested without overlap";
     default: return "unknown status";
   }
 }

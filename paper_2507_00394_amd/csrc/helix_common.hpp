@@ -47,8 +47,10 @@ __device__ __forceinline__ float half_sum(float x) {
 //   - ds_read_b64_tr_b16 by 32 lanes on 4 consecutive rows x 64 contiguous bytes.
 template <int D>
 __device__ __forceinline__ int swizzle(int row) {
+  static_assert(D == 128 || D == 64 || D == 32, "tile widths with a known conflict-free permutation");
   if constexpr (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
-  else return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+  else if constexpr (D == 64) return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+  else return (row >> 2) & 3;   // 64-byte rows: rows r, r+4, r+8, r+12 share banks, so they take different chunks
 }
 template <int D>
 __device__ __forceinline__ int lds_chunk_off(int row, int chunk) {

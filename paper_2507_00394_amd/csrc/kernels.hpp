@@ -33,4 +33,16 @@ hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void
                          const float* lse, const float* delta, void* dq, const BwdMaps& maps,
                          int B, int H, int S, int D, float scale, bool causal, hipStream_t stream);
 
+// Linear layer next to attention: out[M][N] = a[M][K] w[K][N] (bf16, fp32 accumulation) and its
+// backward products da[M][K] = dout[M][N] w[K][N]^T (bf16) and dw[K][N] = a[M][K]^T dout[M][N] (fp32).
+// ld*: elements between consecutive rows.
+hipError_t launch_linear_fwd(const void* a, long long lda, const void* w, long long ldw, void* out, long long ldo,
+                             int M, int K, int N, hipStream_t stream);
+hipError_t launch_linear_bwd_input(const void* dout, long long ldd, const void* w, long long ldw, void* da, long long lda,
+                                   int M, int K, int N, hipStream_t stream);
+// workspace: linear_bwd_workspace_bytes(M, K, N) bytes of device memory (may be 0 bytes / null then).
+size_t linear_bwd_workspace_bytes(int M, int K, int N);
+hipError_t launch_linear_bwd_weight(const void* a, long long lda, const void* dout, long long ldd, float* dw, long long ldw,
+                                    float* workspace, int M, int K, int N, hipStream_t stream);
+
 }  // namespace helix

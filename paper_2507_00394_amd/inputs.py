@@ -138,3 +138,13 @@ def sample_cols(cfg: AttnConfig, n_full: int = 64, n_tail: int = 128, tail: int 
     for _ in range(n_tail):
         tail_cols[heads[int(rng.integers(len(heads)))]].add(int(rng.integers(lo, S)))
     return full, {bh: sorted(c) for bh, c in tail_cols.items() if c}
+
+
+def linear_case_bits(seed: int, M: int, K: int, N: int, w_std: float = 0.02):
+    """bf16 bit patterns of a linear-layer case: a [M,K] ~ N(0,1) (a LayerNorm output),
+    w [K,N] ~ N(0, w_std^2) (GPT-style initialisation), dqkv [M,N] ~ N(0,1)."""
+    out = {}
+    for t, (name, shape, mult) in enumerate((("a", (M, K), 1.0), ("w", (K, N), w_std), ("dqkv", (M, N), 1.0))):
+        g = np.random.Generator(np.random.Philox(key=[(SEED << 32) | (0xFFFF0000 + (seed & 0xFFFF)), 64 + t]))
+        out[name] = float_to_bf16_bits(g.standard_normal(shape, dtype=np.float32) * np.float32(mult))
+    return out

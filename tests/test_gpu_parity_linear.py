@@ -1,0 +1,102 @@
+"""The QKV linear layer on the GPU against the fp64 oracle, and the layer feeding the strided
+attention entry points in place (Section 4.2: the layer runs on the attention stage)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention_ref as A
+from oracle import linear_ref as L
+from paper_2507_00394_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+# bf16 outputs: one rounding of the fp32 sum (relative 2^-9, taken with a factor 2 of margin) plus the
+# fp32 accumulation error, far below 1e-3 of the output's rms at these contraction lengths.
+# fp32 output (dw): accumulation error only.
+
+
+def _check_bf16(name, got, ref):
+    err = np.abs(got - ref)
+    tol = 2.0 ** -8 * np.abs(ref) + 1e-3 * np.sqrt(np.mean(ref ** 2))
+    assert np.isfinite(got).all() and (err <= tol).all(), f"{name}: worst excess {(err - tol).max():.3g}, max err {err.max():.3g}"
+
+
+def _check_f32(name, got, ref):
+    err = np.abs(got - ref)
+    tol = 1e-3 * np.sqrt(np.mean(ref ** 2)) + 1e-5 * np.abs(ref)
+    assert np.isfinite(got).all() and (err <= tol).all(), f"{name}: max err {err.max():.3g}, rms {np.sqrt(np.mean(ref ** 2)):.3g}"
+
+
+@pytest.mark.parametrize("M,K,N", [(32, 128, 128), (300, 256, 384), (1000, 512, 768), (2080, 640, 1920), (4096, 1024, 256)])
+def test_forward(M, K, N):
+    from paper_2507_00394_amd import binding as hx
+    from tests import gpu_util as G
+
+    bits = I.linear_case_bits(M + K + N, M, K, N)
+    a, w = G.to_dev(bits["a"]), G.to_dev(bits["w"])
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    hx.helix_qkv_linear_fwd(a, w, out)
+    torch.cuda.synchronize()
+    ref = L.linear_fwd_ref(I.bf16_bits_to_float(bits["a"]), I.bf16_bits_to_float(bits["w"]))
+    _check_bf16("qkv", G.to_f64(out), ref)
+
+
+@pytest.mark.parametrize("M,K,N", [(32, 128, 128), (320, 256, 384), (992, 512, 768), (2080, 640, 1920), (4096, 1024, 256), (16416, 256, 384)])
+def test_backward(M, K, N):
+    from paper_2507_00394_amd import binding as hx
+    from tests import gpu_util as G
+
+    bits = I.linear_case_bits(7 + M + K + N, M, K, N)
+    a, w, g = G.to_dev(bits["a"]), G.to_dev(bits["w"]), G.to_dev(bits["dqkv"])
+    da = torch.full((M, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dw = torch.full((K, N), float("nan"), dtype=torch.float32, device="cuda")
+    nws = hx.helix_qkv_linear_bwd_workspace_bytes(M, K, N)
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+    hx.helix_qkv_linear_bwd(a, w, g, da, dw, ws)
+    torch.cuda.synchronize()
+    f = {t: I.bf16_bits_to_float(bits[t]) for t in bits}
+    ref = L.linear_bwd_ref(f["a"], f["w"], f["dqkv"])
+    _check_bf16("da", G.to_f64(da), ref["da"])
+    _check_f32("dw", G.to_f64(dw), ref["dw"])
+
+
+def test_padded_leading_dimensions_and_untouched_padding():
+    from paper_2507_00394_amd import binding as hx
+    from tests import gpu_util as G
+
+    M, K, N = 200, 256, 384
+    bits = I.linear_case_bits(99, M, K, N)
+    a_buf = torch.zeros(M, K + 64, dtype=torch.bfloat16, device="cuda"); a = a_buf[:, :K]; a.copy_(G.to_dev(bits["a"]))
+    w = G.to_dev(bits["w"])
+    out_buf = torch.full((M, N + 128), float("nan"), dtype=torch.bfloat16, device="cuda"); out = out_buf[:, 64:64 + N]
+    hx.helix_qkv_linear_fwd(a, w, out)
+    torch.cuda.synchronize()
+    ref = L.linear_fwd_ref(I.bf16_bits_to_float(bits["a"]), I.bf16_bits_to_float(bits["w"]))
+    _check_bf16("qkv", G.to_f64(out.contiguous()), ref)
+    assert torch.isnan(out_buf[:, :64]).all() and torch.isnan(out_buf[:, 64 + N:]).all()
+
+
+def test_layer_feeds_attention_in_place():
+    """a[S*B, h] @ w[h, 3*H*D] lands in an [S, B, 3, H, D] buffer whose q, k, v views go straight
+    into the strided attention forward; O is checked against the oracle on the layer's own
+    (bf16) output values."""
+    from paper_2507_00394_amd import binding as hx
+    from tests import gpu_util as G
+
+    S, B, H, D, hidden = 640, 1, 2, 128, 256
+    bits = I.linear_case_bits(123, S * B, hidden, 3 * H * D, w_std=0.08)
+    a, w = G.to_dev(bits["a"]), G.to_dev(bits["w"])
+    qkv = torch.empty(S, B, 3, H, D, dtype=torch.bfloat16, device="cuda")
+    hx.helix_qkv_linear_fwd(a, w, qkv.view(S * B, 3 * H * D))
+    q, k, v = (qkv[:, :, i].permute(1, 2, 0, 3) for i in range(3))
+    o = torch.empty(S, B, H, D, dtype=torch.bfloat16, device="cuda").permute(1, 2, 0, 3)
+    lse = torch.empty(B, H, S, dtype=torch.float32, device="cuda")
+    scale = D ** -0.5
+    hx.helix_attn_fwd_strided(q, k, v, o, lse, scale, True)
+    torch.cuda.synchronize()
+    ref_qkv = L.linear_fwd_ref(I.bf16_bits_to_float(bits["a"]), I.bf16_bits_to_float(bits["w"]))
+    _check_bf16("qkv", G.to_f64(qkv.view(S * B, -1)), ref_qkv)
+    qf, kf, vf = (G.to_f64(t.contiguous()) for t in (q, k, v))
+    ref_o, ref_lse = A.attn_fwd_ref(qf, kf, vf, scale, True)
+    G.check("o", G.to_f64(o.contiguous()), ref_o)
+    assert np.abs(G.to_f64(lse) - ref_lse).max() <= G.TOL_LSE
