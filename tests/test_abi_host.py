@@ -112,6 +112,23 @@ def test_stride_validation(L):
     assert bwd(good["seq_major"], ws=16) == 6                   # workspace size is checked before the strides
 
 
+def test_linear_layer_validation(L):
+    p = ctypes.c_void_p(0x10000)
+    fwd = lambda M=64, K=128, N=256, lda=128, ldw=256, ldo=256, a=p: L.helix_qkv_linear_fwd(a, lda, p, ldw, p, ldo, M, K, N, None)
+    assert fwd(a=None) == 1 and fwd(a=ctypes.c_void_p(0x10008)) == 4
+    assert fwd(M=0) == 2 and fwd(K=96) == 2 and fwd(N=200) == 2
+    assert fwd(lda=120) == 8 and fwd(ldw=260) == 8 and fwd(ldo=(1 << 23) + 8) == 8
+    bwd = lambda M=4096, ws=p, wsb=1 << 30, ldda=128: L.helix_qkv_linear_bwd(p, 128, p, 128, p, 128, p, ldda, p, 128, ws, wsb, M, 128, 128, None)
+    assert bwd(M=4100) == 2                       # the weight gradient contracts over M in stages of 32
+    assert bwd(ldda=64) == 8
+    need = hx.helix_qkv_linear_bwd_workspace_bytes(4096, 128, 128)
+    assert need == 2 * 128 * 128 * 4              # two parts of 2048 tokens
+    assert bwd(ws=None) == 1 and bwd(ws=ctypes.c_void_p(0x10010)) == 4 and bwd(wsb=need - 1) == 6
+    assert hx.helix_qkv_linear_bwd_workspace_bytes(1024, 128, 128) == 0      # too few tokens to split
+    assert hx.helix_qkv_linear_bwd_workspace_bytes(131072, 4096, 1536) == 6 * 4096 * 1536 * 4
+    assert hx.helix_qkv_linear_bwd_workspace_bytes(4096, 100, 128) == 0      # invalid shape
+
+
 def test_binding_refuses_cpu_tensors(L):
     import torch
 
