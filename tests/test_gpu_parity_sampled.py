@@ -87,3 +87,30 @@ def test_two_micro_batches_equal_two_calls_and_runs_repeat():
         one = G.run_fwd_bwd({t: np.ascontiguousarray(bits[t][b:b + 1]) for t in bits}, cfg.scale, True)
         for n in ("o", "lse", "dq", "dk", "dv"):
             assert torch.equal(one[n][0], both[n][b]), (n, b)
+
+
+def test_beyond_the_longest_sequence_of_the_paper():
+    """S = 2 * 131072 + 45 (ragged, twice the paper's longest sequence), two heads: sampled query
+    rows and the key columns of the last 512 positions against the oracle."""
+    from tests import gpu_util as G
+
+    S, H, D = 2 * 131072 + 45, 2, 128
+    cfg, bits = I.random_case_bits(777, 1, H, S, D)
+    out = G.run_fwd_bwd(bits, cfg.scale, True)
+    flat = {t: bits[t].reshape(H, S, D) for t in bits}
+    rows = sorted({0, 1, 63, 64, 255, 256, 4095, 131071, 131072, 200000, S - 257, S - 46, S - 45, S - 2, S - 1})
+    worst = {}
+    for bh in range(H):
+        f = {t: I.bf16_bits_to_float(flat[t][bh]) for t in ("q", "k", "v", "dO")}
+        o, lse, dq = A.head_rows(f["q"], f["k"], f["v"], f["dO"], rows, cfg.scale, True)
+        sel = torch.tensor(rows, device="cuda")
+        G.check("o", G.to_f64(out["o"][0, bh][sel]), o)
+        G.check("dq", G.to_f64(out["dq"][0, bh][sel]), dq)
+        assert np.abs(G.to_f64(out["lse"][0, bh][sel]) - lse).max() <= G.TOL_LSE
+        start = S - 512
+        lse_t, delta_t = A.head_stats(f["q"], f["k"], f["v"], f["dO"], cfg.scale, True, row_start=start)
+        cols = sorted({start, start + 1, start + 100, S - 129, S - 128, S - 46, S - 45, S - 33, S - 2, S - 1})
+        dk, dv = A.head_cols(f["q"], f["k"], f["v"], f["dO"], cols, lse_t, delta_t, cfg.scale, True, row_start=start)
+        csel = torch.tensor(cols, device="cuda")
+        worst[bh] = (G.check("dk", G.to_f64(out["dk"][0, bh][csel]), dk), G.check("dv", G.to_f64(out["dv"][0, bh][csel]), dv))
+    print("beyond-paper case, (max, mean) errors of dk, dv per head:", worst, flush=True)
