@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch at config 4 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
 # copy-kernel calibration (profiles/hbm_traffic_cfg4.md): fetched x2.00 + written x1.00.
 TRAFFIC_CFG4_BYTES = {"fwd": (1.01e7 * 2 + 1.065e6) * 1024, "dkdv": (1.86e7 * 2 + 2.097e6) * 1024,
-                      "dq": (1.25e7 * 2 + 1.049e6) * 1024}
+                      "dq": (1.18e7 * 2 + 1.049e6) * 1024}
 # Sustained rate of a pure v_mfma_f32_32x32x16_bf16 loop on the same chip (profiles/kernel_stats_cfg4.md):
 # the clock drops under the power limit when the operands are random.
 SUSTAINED_MFMA_TFLOPS = {"constant_operands": 2250.0, "random_operands": 1760.0}
@@ -55,6 +55,9 @@ def parse():
                     help="time the QKV linear layer of the attention stage (Section 4.2) instead of attention: "
                          "M = --seq tokens, K = --hidden, N = 3 * --share-heads * 128 columns (default 4 heads)")
     ap.add_argument("--hidden", type=int, default=4096)
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="before anything is timed, copy this many MiB device to device once: a plain copy of known "
+                         "size against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=49152)
     return ap.parse_args()
@@ -282,6 +285,11 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.calibration_copy_mib > 0:
+        src = torch.zeros(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev)
+        torch.empty_like(src).copy_(src)
+        torch.cuda.synchronize()
+        del src
     if args.qkv_linear:
         return linear_bench(args)
     if args.share_heads:
