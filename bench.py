@@ -260,7 +260,9 @@ def linear_bench(args):
            "pct_of_bf16_mfma_peak": 100 * value / peak_tflops, "fwd_ms": ms_fwd, "bwd_ms": ms_bwd,
            "fwd_tflops": flops / ms_fwd / 1e9, "bwd_tflops": 2 * flops / ms_bwd / 1e9,
            "roofline": {"bound": "mfma", "kernel": "gemm (forward)", "achieved": flops / ms_fwd / 1e9, "peak": 2500.0,
-                        "unit": "TFLOP/s", "frac": flops / ms_fwd / 1e9 / 2500.0, "traffic": None,
+                        "unit": "TFLOP/s", "frac": flops / ms_fwd / 1e9 / 2500.0,
+                        # profiles/hbm_traffic_qkv_linear.md: FETCH_SIZE x2 + WRITE_SIZE x1 of the forward product
+                        "traffic": (1.21e6 * 2 + 3.933e5) * 1024 if (M, K, N) == (131072, 4096, 1536) else None,
                         "flops_per_launch": flops, "avg_launch_ms": ms_fwd}}
     if not args.no_cpu_baseline:
         from oracle import linear_ref as L
