@@ -157,7 +157,7 @@ int helix_attn_bwd_strided(const void* q, const helix_strides* q_strides,
  *             dw[K][N]  = a[M][K]^T * dqkv[M][N]                 fp32 out (overwritten, not accumulated)
  * M = S*B rows (tokens), K = hidden size, N = this GPU's share of the 3h output columns.
  * All matrices are row-major device memory, 16-byte aligned; ld* is the number of elements
- * between consecutive rows (>= the row length, a multiple of 8, at most 2^23).  K and N must be
+ * between consecutive rows (>= the row length, a multiple of 8, at most 2^22).  K and N must be
  * multiples of 128; M is arbitrary for the forward and a multiple of 32 for the backward
  * (HELIX_ERR_BAD_SHAPE otherwise; HELIX_ERR_BAD_STRIDE for a bad ld).  No bias (Table 1 neglects it).
  * The backward cuts the weight gradient's contraction over the M tokens into parts that run side

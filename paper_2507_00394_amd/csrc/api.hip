@@ -87,7 +87,8 @@ int check_linear(int M, int K, int N, bool need_m32, std::initializer_list<std::
   if ((K & 127) || (N & 127) || (need_m32 && (M & 31))) return HELIX_ERR_BAD_SHAPE;
   if (K > (1 << 20) || N > (1 << 20) || (long long)((M + 255) / 256 + 8) * ((N > K ? N : K) / 128) > 0x7fffffffLL / 8) return HELIX_ERR_BAD_SHAPE;
   for (const auto& ld : lds)
-    if (ld.first < ld.second || (ld.first & 7) || ld.first > (1 << 23)) return HELIX_ERR_BAD_STRIDE;
+    // 255 rows of a stage tile times the row pitch in bytes stays below 2^31: lane offsets of the copies fit 32 bits with room to spare
+    if (ld.first < ld.second || (ld.first & 7) || ld.first > (1 << 22)) return HELIX_ERR_BAD_STRIDE;
   return HELIX_OK;
 }
 
