@@ -103,3 +103,23 @@ def test_full_attention_strided():
     assert torch.equal(lse, out["lse"])
     for n in ("o", "dq", "dk", "dv"):
         assert torch.equal(views[n].contiguous().view(torch.int16), out[n].view(torch.int16)), n
+
+
+def test_row_stride_of_sixteen_mebibytes():
+    """Rows 2^23 elements apart (the tile copies then use lane offsets of up to 1e9 bytes and 64-bit
+    tile bases): same bits as the contiguous call."""
+    from tests import gpu_util as G
+
+    B, H, S, D = 1, 2, 100, 128
+    row = 1 << 23
+    cfg, bits = I.random_case_bits(4400, B, H, S, D)
+    out = _contiguous_reference(bits, cfg.scale, True)
+    buf = torch.empty((S - 1) * row + 8 * H * D, dtype=torch.bfloat16, device="cuda")     # 1.6 GiB, mostly untouched
+    names = ("q", "k", "v", "dO", "o", "dq", "dk", "dv")
+    views = {n: torch.as_strided(buf, (B, H, S, D), (0, D, row, 1), storage_offset=i * H * D) for i, n in enumerate(names)}
+    for t in ("q", "k", "v", "dO"):
+        views[t].copy_(G.to_dev(bits[t]))
+    lse = _run_strided(views, (B, H, S), cfg.scale, True)
+    assert torch.equal(lse, out["lse"])
+    for n in ("o", "dq", "dk", "dv"):
+        assert torch.equal(views[n].contiguous().view(torch.int16), out[n].view(torch.int16)), n
