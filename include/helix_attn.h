@@ -160,11 +160,11 @@ int helix_attn_bwd_strided(const void* q, const helix_strides* q_strides,
  * between consecutive rows (>= the row length, a multiple of 8, at most 2^22).  K and N must be
  * multiples of 128; M is arbitrary for the forward and a multiple of 32 for the backward
  * (HELIX_ERR_BAD_SHAPE otherwise; HELIX_ERR_BAD_STRIDE for a bad ld).  No bias (Table 1 neglects it).
- * The backward cuts the weight gradient's contraction over the M tokens into parts that run side
- * by side and are then summed in a fixed order (bit-reproducible, no atomics); the parts live in
- * `workspace`: device memory of at least helix_qkv_linear_bwd_workspace_bytes(M, K, N) bytes,
- * 256-byte aligned, owned by the caller, contents undefined afterwards; it may be NULL when that
- * size is 0 (HELIX_ERR_NULL_POINTER / _MISALIGNED / _WORKSPACE otherwise).
+ * The backward keeps a transposed copy of w and cuts the weight gradient's contraction over the M
+ * tokens into parts that run side by side and are then summed in a fixed order (bit-reproducible,
+ * no atomics); both live in `workspace`: device memory of at least
+ * helix_qkv_linear_bwd_workspace_bytes(M, K, N) bytes, 256-byte aligned, owned by the caller,
+ * contents undefined afterwards (HELIX_ERR_NULL_POINTER / _MISALIGNED / _WORKSPACE otherwise).
  * Asynchronous on `stream`; nothing is allocated; inputs are not written. */
 int helix_qkv_linear_fwd(const void* a, long long lda, const void* w, long long ldw,
                          void* qkv, long long ldqkv, int M, int K, int N, void* stream);
@@ -172,8 +172,7 @@ int helix_qkv_linear_bwd(const void* a, long long lda, const void* w, long long 
                          const void* dqkv, long long lddqkv, void* da, long long ldda,
                          float* dw, long long lddw, void* workspace, size_t workspace_bytes,
                          int M, int K, int N, void* stream);
-/* Bytes of scratch helix_qkv_linear_bwd needs (0 for an invalid shape or when no split is used).
- * Pure host arithmetic. */
+/* Bytes of scratch helix_qkv_linear_bwd needs (0 for an invalid shape).  Pure host arithmetic. */
 size_t helix_qkv_linear_bwd_workspace_bytes(int M, int K, int N);
 
 /* Whether `strides` (NULL: contiguous) is acceptable for a [B, H, S, D] view: HELIX_OK,

@@ -243,7 +243,7 @@ def helix_qkv_linear_bwd_workspace_bytes(M, K, N) -> int:
 
 def helix_qkv_linear_bwd(a, w, dqkv, da, dw, workspace=None, stream=None):
     """da[M,K] <- dqkv @ w^T (bf16), dw[K,N] <- a^T @ dqkv (fp32); workspace: uint8 CUDA tensor of
-    helix_qkv_linear_bwd_workspace_bytes(M, K, N) bytes (None if that is 0)."""
+    helix_qkv_linear_bwd_workspace_bytes(M, K, N) bytes."""
     M, K = a.shape
     N = w.shape[1]
     (pa, lda), (pw, ldw), (pg, ldg) = _matrix("a", a, M, K), _matrix("w", w, K, N), _matrix("dqkv", dqkv, M, N)

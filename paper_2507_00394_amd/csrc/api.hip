@@ -233,14 +233,13 @@ int helix_qkv_linear_bwd(const void* a, long long lda, const void* w, long long 
                          int M, int K, int N, void* stream) {
   HELIX_TRY(check_bf16_ptrs(a, w, dqkv, (const void*)da, (const void*)dw));
   HELIX_TRY(check_linear(M, K, N, true, {{lda, K}, {ldw, N}, {lddqkv, N}, {ldda, K}, {lddw, N}}));
-  const size_t need = helix_qkv_linear_bwd_workspace_bytes(M, K, N);
-  if (need > 0) {
-    if (!workspace) return HELIX_ERR_NULL_POINTER;
-    if (!aligned(workspace, 256)) return HELIX_ERR_MISALIGNED;
-    if (workspace_bytes < need) return HELIX_ERR_WORKSPACE;
-  }
-  HELIX_TRY(launched(helix::launch_linear_bwd_input(dqkv, lddqkv, w, ldw, da, ldda, M, K, N, (hipStream_t)stream)));
-  return launched(helix::launch_linear_bwd_weight(a, lda, dqkv, lddqkv, dw, lddw, static_cast<float*>(workspace), M, K, N,
+  if (!workspace) return HELIX_ERR_NULL_POINTER;
+  if (!aligned(workspace, 256)) return HELIX_ERR_MISALIGNED;
+  if (workspace_bytes < helix_qkv_linear_bwd_workspace_bytes(M, K, N)) return HELIX_ERR_WORKSPACE;
+  char* ws = static_cast<char*>(workspace);
+  HELIX_TRY(launched(helix::launch_linear_bwd_input(dqkv, lddqkv, w, ldw, da, ldda, ws, M, K, N, (hipStream_t)stream)));
+  return launched(helix::launch_linear_bwd_weight(a, lda, dqkv, lddqkv, dw, lddw,
+                                                  reinterpret_cast<float*>(ws + helix::linear_bwd_wt_bytes(K, N)), M, K, N,
                                                   (hipStream_t)stream));
 }
 

@@ -38,10 +38,12 @@ hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void
 // ld*: elements between consecutive rows.
 hipError_t launch_linear_fwd(const void* a, long long lda, const void* w, long long ldw, void* out, long long ldo,
                              int M, int K, int N, hipStream_t stream);
-hipError_t launch_linear_bwd_input(const void* dout, long long ldd, const void* w, long long ldw, void* da, long long lda,
-                                   int M, int K, int N, hipStream_t stream);
-// workspace: linear_bwd_workspace_bytes(M, K, N) bytes of device memory (may be 0 bytes / null then).
+// The backward's workspace (linear_bwd_workspace_bytes) holds w^T in its first linear_bwd_wt_bytes(K, N)
+// bytes and the partial weight gradients after them.
 size_t linear_bwd_workspace_bytes(int M, int K, int N);
+size_t linear_bwd_wt_bytes(int K, int N);
+hipError_t launch_linear_bwd_input(const void* dout, long long ldd, const void* w, long long ldw, void* da, long long lda,
+                                   void* wt, int M, int K, int N, hipStream_t stream);
 hipError_t launch_linear_bwd_weight(const void* a, long long lda, const void* dout, long long ldd, float* dw, long long ldw,
                                     float* workspace, int M, int K, int N, hipStream_t stream);
 

@@ -5,7 +5,7 @@
 //     C[i][j] = sum_r X(i, r) * Y(r, j),       fp32 accumulation
 //
 //   forward          qkv[M][N] = a[M][K]    * w[K][N]      X stored [i][r],  Y stored [r][j]
-//   backward input   da[M][K]  = dqkv[M][N] * w[K][N]^T    X stored [i][r],  Y stored [j][r]
+//   backward input   da[M][K]  = dqkv[M][N] * w[K][N]^T    X stored [i][r],  Y stored [r][j] after a transposing copy of w
 //   backward weight  dw[K][N]  = a[M][K]^T  * dqkv[M][N]   X stored [r][i],  Y stored [r][j]
 //
 // A workgroup of 4 waves (one per SIMD) owns a 256 x 256 tile of C; wave (wi, wj) owns 128 rows i
@@ -237,9 +237,30 @@ hipError_t launch_linear_fwd(const void* a, long long lda, const void* w, long l
                              int M, int K, int N, hipStream_t stream) {
   return launch_gemm<false, true, __bf16>(a, lda, w, ldw, out, ldo, M, N, K, 1, K, 0, stream);
 }
+// out[c][r] = in[r][c] for a [rows][cols] bf16 matrix (both extents multiples of 64).
+__global__ void __launch_bounds__(256) transpose_kernel(const __bf16* __restrict__ in, long long ld_in,
+                                                        __bf16* __restrict__ out, long long ld_out) {
+  __shared__ __bf16 tile[64][66];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const size_t r0 = (size_t)blockIdx.y * 64, c0 = (size_t)blockIdx.x * 64;
+#pragma unroll
+  for (int i = 0; i < 16; i++) tile[ty * 16 + i][tx] = in[(r0 + ty * 16 + i) * ld_in + c0 + tx];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; i++) out[(c0 + ty * 16 + i) * ld_out + r0 + tx] = tile[tx][ty * 16 + i];
+}
+
+// Input gradient da = dout * w^T.  With w as stored ([K][N], contraction index n contiguous) both
+// operands would reach LDS in 64-byte row pieces, the least efficient pattern of the copy path
+// (measured 30 % slower than the forward product); a transposed copy of the small weight matrix
+// (w^T [N][K], in the workspace) turns it into the forward's operand combination.
 hipError_t launch_linear_bwd_input(const void* dout, long long ldd, const void* w, long long ldw, void* da, long long lda,
-                                   int M, int K, int N, hipStream_t stream) {
-  return launch_gemm<false, false, __bf16>(dout, ldd, w, ldw, da, lda, M, K, N, 1, N, 0, stream);
+                                   void* wt, int M, int K, int N, hipStream_t stream) {
+  hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)(N / 64), (unsigned)(K / 64)), dim3(256), 0, stream,
+                     (const __bf16*)w, ldw, (__bf16*)wt, (long long)K);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_gemm<false, true, __bf16>(dout, ldd, wt, K, da, lda, M, K, N, 1, N, 0, stream);
 }
 
 // The weight gradient has few output tiles and a long contraction (over all M tokens), so the
@@ -253,9 +274,11 @@ int linear_bwd_weight_parts(int M, int K, int N) {
   if (parts > 32) parts = 32;
   return (int)parts;
 }
+// Workspace of the backward: w^T (bf16 [N][K], rounded up to 256 bytes), then the partial weight gradients.
+size_t linear_bwd_wt_bytes(int K, int N) { return ((size_t)K * N * 2 + 255) & ~(size_t)255; }
 size_t linear_bwd_workspace_bytes(int M, int K, int N) {
   const int parts = linear_bwd_weight_parts(M, K, N);
-  return parts > 1 ? (size_t)parts * K * N * sizeof(float) : 0;
+  return linear_bwd_wt_bytes(K, N) + (parts > 1 ? (size_t)parts * K * N * sizeof(float) : 0);
 }
 hipError_t launch_linear_bwd_weight(const void* a, long long lda, const void* dout, long long ldd, float* dw, long long ldw,
                                     float* workspace, int M, int K, int N, hipStream_t stream) {

@@ -122,10 +122,10 @@ def test_linear_layer_validation(L):
     assert bwd(M=4100) == 2                       # the weight gradient contracts over M in stages of 32
     assert bwd(ldda=64) == 8
     need = hx.helix_qkv_linear_bwd_workspace_bytes(4096, 128, 128)
-    assert need == 2 * 128 * 128 * 4              # two parts of 2048 tokens
+    assert need == 128 * 128 * 2 + 2 * 128 * 128 * 4   # w^T, then two parts of 2048 tokens
     assert bwd(ws=None) == 1 and bwd(ws=ctypes.c_void_p(0x10010)) == 4 and bwd(wsb=need - 1) == 6
-    assert hx.helix_qkv_linear_bwd_workspace_bytes(1024, 128, 128) == 0      # too few tokens to split
-    assert hx.helix_qkv_linear_bwd_workspace_bytes(131072, 4096, 1536) == 6 * 4096 * 1536 * 4
+    assert hx.helix_qkv_linear_bwd_workspace_bytes(1024, 128, 128) == 128 * 128 * 2     # too few tokens to split: w^T only
+    assert hx.helix_qkv_linear_bwd_workspace_bytes(131072, 4096, 1536) == 4096 * 1536 * 2 + 6 * 4096 * 1536 * 4
     assert hx.helix_qkv_linear_bwd_workspace_bytes(4096, 100, 128) == 0      # invalid shape
 
 

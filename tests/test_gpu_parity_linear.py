@@ -51,7 +51,7 @@ def test_backward(M, K, N):
     da = torch.full((M, K), float("nan"), dtype=torch.bfloat16, device="cuda")
     dw = torch.full((K, N), float("nan"), dtype=torch.float32, device="cuda")
     nws = hx.helix_qkv_linear_bwd_workspace_bytes(M, K, N)
-    ws = torch.empty(nws, dtype=torch.uint8, device="cuda") if nws else None
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
     hx.helix_qkv_linear_bwd(a, w, g, da, dw, ws)
     torch.cuda.synchronize()
     f = {t: I.bf16_bits_to_float(bits[t]) for t in bits}
