@@ -307,7 +307,7 @@ def main():
     B, H, S, D = q.shape
     o = torch.empty_like(q); lse = torch.empty((B, H, S), dtype=torch.float32, device=dev)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
-    delta = torch.empty_like(lse)
+    stats = torch.empty(hx.helix_attn_bwd_workspace_bytes(B, H, S, D), dtype=torch.uint8, device=dev)
     stages = ["fwd", "preprocess", "delta_head", "dkdv", "dq"]
 
     def step(events=None):
@@ -315,12 +315,12 @@ def main():
             if events is not None:
                 events[i].record()
         mark(0); hx.helix_attn_fwd(q, k, v, o, lse, cfg.scale, cfg.causal)
-        mark(1); hx.helix_attn_bwd_preprocess(o, g, delta)
+        mark(1); hx.helix_attn_bwd_preprocess(o, g, lse, stats)
         mark(2)
         if cfg.causal:
-            hx.helix_attn_bwd_delta_head(q, k, v, g, lse, delta, hx.DELTA_HEAD_ROWS, cfg.scale, True)
-        mark(3); hx.helix_attn_bwd_dkdv(q, k, v, g, lse, delta, dk, dv, cfg.scale, cfg.causal)
-        mark(4); hx.helix_attn_bwd_dq(q, k, v, g, lse, delta, dq, cfg.scale, cfg.causal)
+            hx.helix_attn_bwd_delta_head(q, k, v, g, lse, stats, hx.DELTA_HEAD_ROWS, cfg.scale, True)
+        mark(3); hx.helix_attn_bwd_dkdv(q, k, v, g, stats, dk, dv, cfg.scale, cfg.causal)
+        mark(4); hx.helix_attn_bwd_dq(q, k, v, g, stats, dq, cfg.scale, cfg.causal)
         mark(5)
 
     if args.overlap != "none":
@@ -344,7 +344,7 @@ def main():
     # dominant kernel: the dK/dV pass (4 contractions = 8*D FLOPs per unmasked pair)
     dom = max(("fwd", 4), ("dkdv", 8), ("dq", 6), key=lambda kv: ms[kv[0]])
     dom_tflops = dom[1] * unit / (ms[dom[0]] * 1e-3) / 1e12
-    pre_bytes = 2 * q.numel() * 2 + lse.numel() * 4
+    pre_bytes = 2 * q.numel() * 2 + 3 * lse.numel() * 4   # reads O, dO, LSE; writes -delta and LSE*log2(e)
     out = {
         "metric": "causal attn fwd+bwd TFLOP/s @H=32,D=128,S=128k; % of bf16 MFMA peak",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

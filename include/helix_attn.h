@@ -82,37 +82,42 @@ int helix_attn_fwd(const void* q, const void* k, const void* v, void* o, float* 
  *   dO              : in,  bf16 [B, H, S, D]
  *   dq, dk, dv      : out, bf16 [B, H, S, D]
  *   workspace       : device scratch of at least helix_attn_bwd_workspace_bytes(B,H,S,D)
- *                     bytes, 256-byte aligned, owned by the caller; holds delta (fp32 [B,H,S])
- *                     between the kernels; contents undefined afterwards. */
+ *                     bytes, 256-byte aligned, owned by the caller; holds the row statistics
+ *                     (see below) between the kernels; contents undefined afterwards. */
 int helix_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
                    const void* dO, void* dq, void* dk, void* dv,
                    void* workspace, size_t workspace_bytes,
                    int B, int H, int S, int D, float scale, int causal, void* stream);
 
-/* Bytes of scratch helix_attn_bwd needs: B*H*S*4 rounded up to 256.  Returns 0 for an
- * invalid shape.  Pure host arithmetic. */
+/* Bytes of scratch helix_attn_bwd needs: two fp32 planes [B, H, S], each rounded up to 256
+ * bytes.  Returns 0 for an invalid shape.  Pure host arithmetic. */
 size_t helix_attn_bwd_workspace_bytes(int B, int H, int S, int D);
 
 /* The stages of helix_attn_bwd as separate calls, for per-kernel timing and profiling.
- * Same conventions; `delta` is fp32 [B, H, S] on the device.
- *   preprocess : delta <- rowsum(dO * O)                      (memory bound)
- *   delta_head : delta_i <- sum_j p_ij * (dO_i . v_j) for query rows i < rows of every head,
- *                overwriting those entries.  The two expressions are equal in exact
- *                arithmetic; the first rows of a causal head attend to few keys, so O is
- *                large there and its bf16 rounding would dominate the error of delta.
- *   dkdv       : dk, dv from q, k, v, dO, lse, delta
- *   dq         : dq     from q, k, v, dO, lse, delta */
+ * Same conventions.  `stats` is the backward's workspace (helix_attn_bwd_workspace_bytes
+ * bytes, 256-byte aligned, device): plane 0 holds -delta_i = -sum_d dO_id * O_id, plane 1
+ * holds lse_i * log2(e), both fp32 [B, H, S]; the second plane starts half way into the
+ * buffer.  The gradient passes take the statistics in this form so that they spend no
+ * vector instruction per score element on them (-delta is the initial accumulator of the
+ * dO V^T product, and the probabilities are 2^(scale*log2(e)*s - lse*log2(e))).
+ *   preprocess : stats <- (-rowsum(dO * O), lse * log2(e))               (memory bound)
+ *   delta_head : -delta_i <- -sum_j p_ij * (dO_i . v_j) for query rows i < rows of every
+ *                head, overwriting those entries of plane 0.  The two expressions are equal
+ *                in exact arithmetic; the first rows of a causal head attend to few keys, so
+ *                O is large there and its bf16 rounding would dominate the error of delta.
+ *   dkdv       : dk, dv from q, k, v, dO, stats
+ *   dq         : dq     from q, k, v, dO, stats */
 #define HELIX_DELTA_HEAD_ROWS 2048
-int helix_attn_bwd_preprocess(const void* o, const void* dO, float* delta,
+int helix_attn_bwd_preprocess(const void* o, const void* dO, const float* lse, void* stats,
                               int B, int H, int S, int D, void* stream);
 int helix_attn_bwd_delta_head(const void* q, const void* k, const void* v, const void* dO,
-                              const float* lse, float* delta, int rows,
+                              const float* lse, void* stats, int rows,
                               int B, int H, int S, int D, float scale, int causal, void* stream);
 int helix_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* dO,
-                        const float* lse, const float* delta, void* dk, void* dv,
+                        const void* stats, void* dk, void* dv,
                         int B, int H, int S, int D, float scale, int causal, void* stream);
 int helix_attn_bwd_dq(const void* q, const void* k, const void* v, const void* dO,
-                      const float* lse, const float* delta, void* dq,
+                      const void* stats, void* dq,
                       int B, int H, int S, int D, float scale, int causal, void* stream);
 
 /* Compute-unit count and peak engine clock (kHz) of the current HIP device, the two

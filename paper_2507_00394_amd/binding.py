@@ -61,10 +61,10 @@ def lib() -> ctypes.CDLL:
         L.helix_qkv_linear_bwd.restype = i
         L.helix_attn_bwd_workspace_bytes.argtypes = [i, i, i, i]
         L.helix_attn_bwd_workspace_bytes.restype = sz
-        L.helix_attn_bwd_preprocess.argtypes = [vp, vp, fp, i, i, i, i, vp]
-        L.helix_attn_bwd_delta_head.argtypes = [vp, vp, vp, vp, fp, fp, i, i, i, i, i, f, i, vp]
-        L.helix_attn_bwd_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, vp, vp, i, i, i, i, f, i, vp]
-        L.helix_attn_bwd_dq.argtypes = [vp, vp, vp, vp, fp, fp, vp, i, i, i, i, f, i, vp]
+        L.helix_attn_bwd_preprocess.argtypes = [vp, vp, fp, vp, i, i, i, i, vp]
+        L.helix_attn_bwd_delta_head.argtypes = [vp, vp, vp, vp, fp, vp, i, i, i, i, i, f, i, vp]
+        L.helix_attn_bwd_dkdv.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, f, i, vp]
+        L.helix_attn_bwd_dq.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, f, i, vp]
         L.helix_status_string.argtypes = [i]
         L.helix_status_string.restype = ctypes.c_char_p
         L.helix_attn_version.argtypes = []
@@ -184,41 +184,50 @@ def helix_attn_bwd_strided(q, k, v, o, lse, dO, dq, dk, dv, workspace, scale, ca
                                         int(causal), _stream(stream)), "helix_attn_bwd_strided")
 
 
-def helix_attn_bwd_preprocess(o, dO, delta, stream=None):
+def _check_stats(stats, B, H, S, D):
+    """The backward's workspace as the stage calls see it: a uint8 CUDA tensor of at least
+    helix_attn_bwd_workspace_bytes bytes (plane 0: -delta, plane 1: lse * log2(e))."""
+    if stats.dtype != torch.uint8 or not stats.is_cuda or not stats.is_contiguous() or \
+            stats.numel() < helix_attn_bwd_workspace_bytes(B, H, S, D):
+        raise ValueError("stats: need a contiguous CUDA uint8 tensor of helix_attn_bwd_workspace_bytes(B, H, S, D) bytes")
+
+
+def helix_attn_bwd_preprocess(o, dO, lse, stats, stream=None):
     B, H, S, D = o.shape
-    _check_bf16("o", o, (B, H, S, D)); _check_bf16("dO", dO, (B, H, S, D)); _check_f32("delta", delta, (B, H, S))
-    _raise(lib().helix_attn_bwd_preprocess(_ptr(o), _ptr(dO), _ptr(delta), B, H, S, D, _stream(stream)),
+    _check_bf16("o", o, (B, H, S, D)); _check_bf16("dO", dO, (B, H, S, D)); _check_f32("lse", lse, (B, H, S))
+    _check_stats(stats, B, H, S, D)
+    _raise(lib().helix_attn_bwd_preprocess(_ptr(o), _ptr(dO), _ptr(lse), _ptr(stats), B, H, S, D, _stream(stream)),
            "helix_attn_bwd_preprocess")
 
 
 DELTA_HEAD_ROWS = 2048
 
 
-def helix_attn_bwd_delta_head(q, k, v, dO, lse, delta, rows, scale, causal=True, stream=None):
+def helix_attn_bwd_delta_head(q, k, v, dO, lse, stats, rows, scale, causal=True, stream=None):
     B, H, S, D = q.shape
     for n, t in (("q", q), ("k", k), ("v", v), ("dO", dO)):
         _check_bf16(n, t, (B, H, S, D))
-    _check_f32("lse", lse, (B, H, S)); _check_f32("delta", delta, (B, H, S))
-    _raise(lib().helix_attn_bwd_delta_head(_ptr(q), _ptr(k), _ptr(v), _ptr(dO), _ptr(lse), _ptr(delta), int(rows),
+    _check_f32("lse", lse, (B, H, S)); _check_stats(stats, B, H, S, D)
+    _raise(lib().helix_attn_bwd_delta_head(_ptr(q), _ptr(k), _ptr(v), _ptr(dO), _ptr(lse), _ptr(stats), int(rows),
                                            B, H, S, D, float(scale), int(causal), _stream(stream)),
            "helix_attn_bwd_delta_head")
 
 
-def helix_attn_bwd_dkdv(q, k, v, dO, lse, delta, dk, dv, scale, causal=True, stream=None):
+def helix_attn_bwd_dkdv(q, k, v, dO, stats, dk, dv, scale, causal=True, stream=None):
     B, H, S, D = q.shape
     for n, t in (("q", q), ("k", k), ("v", v), ("dO", dO), ("dk", dk), ("dv", dv)):
         _check_bf16(n, t, (B, H, S, D))
-    _check_f32("lse", lse, (B, H, S)); _check_f32("delta", delta, (B, H, S))
-    _raise(lib().helix_attn_bwd_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(dO), _ptr(lse), _ptr(delta), _ptr(dk), _ptr(dv),
+    _check_stats(stats, B, H, S, D)
+    _raise(lib().helix_attn_bwd_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(dO), _ptr(stats), _ptr(dk), _ptr(dv),
                                      B, H, S, D, float(scale), int(causal), _stream(stream)), "helix_attn_bwd_dkdv")
 
 
-def helix_attn_bwd_dq(q, k, v, dO, lse, delta, dq, scale, causal=True, stream=None):
+def helix_attn_bwd_dq(q, k, v, dO, stats, dq, scale, causal=True, stream=None):
     B, H, S, D = q.shape
     for n, t in (("q", q), ("k", k), ("v", v), ("dO", dO), ("dq", dq)):
         _check_bf16(n, t, (B, H, S, D))
-    _check_f32("lse", lse, (B, H, S)); _check_f32("delta", delta, (B, H, S))
-    _raise(lib().helix_attn_bwd_dq(_ptr(q), _ptr(k), _ptr(v), _ptr(dO), _ptr(lse), _ptr(delta), _ptr(dq),
+    _check_stats(stats, B, H, S, D)
+    _raise(lib().helix_attn_bwd_dq(_ptr(q), _ptr(k), _ptr(v), _ptr(dO), _ptr(stats), _ptr(dq),
                                    B, H, S, D, float(scale), int(causal), _stream(stream)), "helix_attn_bwd_dq")
 
 

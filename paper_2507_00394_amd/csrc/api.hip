@@ -77,8 +77,18 @@ helix::BwdMaps contiguous_bwd(int H, int S, int D) {
   return helix::BwdMaps{m, m, m, m, m, m, m, m};
 }
 
+// The backward's row statistics: two fp32 planes [B, H, S], each padded to 256 bytes:
+// plane 0 = -delta = -rowsum(dO o O), plane 1 = lse * log2(e).
+size_t stats_plane_bytes(int B, int H, int S) { return ((size_t)B * H * S * sizeof(float) + 255) & ~(size_t)255; }
+float* neg_delta_plane(void* stats) { return static_cast<float*>(stats); }
+float* lse2_plane(void* stats, int B, int H, int S) { return reinterpret_cast<float*>(static_cast<char*>(stats) + stats_plane_bytes(B, H, S)); }
+int check_stats(const void* stats) {
+  if (!stats) return HELIX_ERR_NULL_POINTER;
+  return aligned(stats, 256) ? HELIX_OK : HELIX_ERR_MISALIGNED;
+}
+
 int run_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
-            void* dq, void* dk, void* dv, float* delta, const helix::BwdMaps& maps,
+            void* dq, void* dk, void* dv, void* stats, const helix::BwdMaps& maps,
             int B, int H, int S, int D, float scale, int causal, hipStream_t st);
 
 // Shapes and leading dimensions of the linear layer; `need_m32`: the product contracts over M.
@@ -132,47 +142,51 @@ int helix_attn_fwd_strided(const void* q, const helix_strides* q_strides, const 
 
 size_t helix_attn_bwd_workspace_bytes(int B, int H, int S, int D) {
   if (check_shape(B, H, S, D) != HELIX_OK) return 0;
-  const size_t n = (size_t)B * H * S * sizeof(float);
-  return (n + 255) & ~(size_t)255;
+  return 2 * stats_plane_bytes(B, H, S);
 }
 
-int helix_attn_bwd_preprocess(const void* o, const void* dO, float* delta,
+int helix_attn_bwd_preprocess(const void* o, const void* dO, const float* lse, void* stats,
                               int B, int H, int S, int D, void* stream) {
   HELIX_TRY(check_bf16_ptrs(o, dO));
-  HELIX_TRY(check_f32_ptrs((const void*)delta));
+  HELIX_TRY(check_f32_ptrs((const void*)lse));
+  HELIX_TRY(check_stats(stats));
   HELIX_TRY(check_shape(B, H, S, D));
-  return launched(helix::launch_bwd_preprocess(o, dO, delta, contiguous_bwd(H, S, D), B, H, S, D, (hipStream_t)stream));
+  return launched(helix::launch_bwd_preprocess(o, dO, lse, neg_delta_plane(stats), lse2_plane(stats, B, H, S),
+                                               contiguous_bwd(H, S, D), B, H, S, D, (hipStream_t)stream));
 }
 
 int helix_attn_bwd_delta_head(const void* q, const void* k, const void* v, const void* dO,
-                              const float* lse, float* delta, int rows,
+                              const float* lse, void* stats, int rows,
                               int B, int H, int S, int D, float scale, int causal, void* stream) {
   HELIX_TRY(check_bf16_ptrs(q, k, v, dO));
-  HELIX_TRY(check_f32_ptrs((const void*)lse, (const void*)delta));
+  HELIX_TRY(check_f32_ptrs((const void*)lse));
+  HELIX_TRY(check_stats(stats));
   HELIX_TRY(check_shape(B, H, S, D));
   HELIX_TRY(check_scale(scale));
   if (rows < 0) return HELIX_ERR_BAD_SHAPE;
-  return launched(helix::launch_bwd_delta_head(q, k, v, dO, lse, delta, contiguous_bwd(H, S, D), B, H, S, D, rows, scale, causal != 0, (hipStream_t)stream));
+  return launched(helix::launch_bwd_delta_head(q, k, v, dO, lse, neg_delta_plane(stats), contiguous_bwd(H, S, D), B, H, S, D, rows, scale, causal != 0, (hipStream_t)stream));
 }
 
 int helix_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* dO,
-                        const float* lse, const float* delta, void* dk, void* dv,
+                        const void* stats, void* dk, void* dv,
                         int B, int H, int S, int D, float scale, int causal, void* stream) {
   HELIX_TRY(check_bf16_ptrs(q, k, v, dO, (const void*)dk, (const void*)dv));
-  HELIX_TRY(check_f32_ptrs((const void*)lse, (const void*)delta));
+  HELIX_TRY(check_stats(stats));
   HELIX_TRY(check_shape(B, H, S, D));
   HELIX_TRY(check_scale(scale));
-  return launched(helix::launch_bwd_dkdv(q, k, v, dO, lse, delta, dk, dv, contiguous_bwd(H, S, D), B, H, S, D, scale, causal != 0, (hipStream_t)stream));
+  void* st = const_cast<void*>(stats);
+  return launched(helix::launch_bwd_dkdv(q, k, v, dO, lse2_plane(st, B, H, S), neg_delta_plane(st), dk, dv, contiguous_bwd(H, S, D), B, H, S, D, scale, causal != 0, (hipStream_t)stream));
 }
 
 int helix_attn_bwd_dq(const void* q, const void* k, const void* v, const void* dO,
-                      const float* lse, const float* delta, void* dq,
+                      const void* stats, void* dq,
                       int B, int H, int S, int D, float scale, int causal, void* stream) {
   HELIX_TRY(check_bf16_ptrs(q, k, v, dO, (const void*)dq));
-  HELIX_TRY(check_f32_ptrs((const void*)lse, (const void*)delta));
+  HELIX_TRY(check_stats(stats));
   HELIX_TRY(check_shape(B, H, S, D));
   HELIX_TRY(check_scale(scale));
-  return launched(helix::launch_bwd_dq(q, k, v, dO, lse, delta, dq, contiguous_bwd(H, S, D), B, H, S, D, scale, causal != 0, (hipStream_t)stream));
+  void* st = const_cast<void*>(stats);
+  return launched(helix::launch_bwd_dq(q, k, v, dO, lse2_plane(st, B, H, S), neg_delta_plane(st), dq, contiguous_bwd(H, S, D), B, H, S, D, scale, causal != 0, (hipStream_t)stream));
 }
 
 int helix_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
@@ -186,7 +200,7 @@ int helix_attn_bwd(const void* q, const void* k, const void* v, const void* o, c
   if (!workspace) return HELIX_ERR_NULL_POINTER;
   if (!aligned(workspace, 256)) return HELIX_ERR_MISALIGNED;
   if (workspace_bytes < helix_attn_bwd_workspace_bytes(B, H, S, D)) return HELIX_ERR_WORKSPACE;
-  return run_bwd(q, k, v, o, lse, dO, dq, dk, dv, static_cast<float*>(workspace), contiguous_bwd(H, S, D),
+  return run_bwd(q, k, v, o, lse, dO, dq, dk, dv, workspace, contiguous_bwd(H, S, D),
                  B, H, S, D, scale, causal, (hipStream_t)stream);
 }
 
@@ -212,7 +226,7 @@ int helix_attn_bwd_strided(const void* q, const helix_strides* q_strides, const 
   HELIX_TRY(to_map(dq_strides, B, H, S, D, &m.dq));
   HELIX_TRY(to_map(dk_strides, B, H, S, D, &m.dk));
   HELIX_TRY(to_map(dv_strides, B, H, S, D, &m.dv));
-  return run_bwd(q, k, v, o, lse, dO, dq, dk, dv, static_cast<float*>(workspace), m, B, H, S, D, scale, causal,
+  return run_bwd(q, k, v, o, lse, dO, dq, dk, dv, workspace, m, B, H, S, D, scale, causal,
                  (hipStream_t)stream);
 }
 
@@ -276,12 +290,14 @@ namespace {
 
 // The whole backward: delta, its refinement on the first rows (causal only), dK/dV, dQ.
 int run_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
-            void* dq, void* dk, void* dv, float* delta, const helix::BwdMaps& maps,
+            void* dq, void* dk, void* dv, void* stats, const helix::BwdMaps& maps,
             int B, int H, int S, int D, float scale, int causal, hipStream_t st) {
-  HELIX_TRY(launched(helix::launch_bwd_preprocess(o, dO, delta, maps, B, H, S, D, st)));
-  if (causal) HELIX_TRY(launched(helix::launch_bwd_delta_head(q, k, v, dO, lse, delta, maps, B, H, S, D, HELIX_DELTA_HEAD_ROWS, scale, true, st)));
-  HELIX_TRY(launched(helix::launch_bwd_dkdv(q, k, v, dO, lse, delta, dk, dv, maps, B, H, S, D, scale, causal != 0, st)));
-  return launched(helix::launch_bwd_dq(q, k, v, dO, lse, delta, dq, maps, B, H, S, D, scale, causal != 0, st));
+  float* nd = neg_delta_plane(stats);
+  float* l2 = lse2_plane(stats, B, H, S);
+  HELIX_TRY(launched(helix::launch_bwd_preprocess(o, dO, lse, nd, l2, maps, B, H, S, D, st)));
+  if (causal) HELIX_TRY(launched(helix::launch_bwd_delta_head(q, k, v, dO, lse, nd, maps, B, H, S, D, HELIX_DELTA_HEAD_ROWS, scale, true, st)));
+  HELIX_TRY(launched(helix::launch_bwd_dkdv(q, k, v, dO, l2, nd, dk, dv, maps, B, H, S, D, scale, causal != 0, st)));
+  return launched(helix::launch_bwd_dq(q, k, v, dO, l2, nd, dq, maps, B, H, S, D, scale, causal != 0, st));
 }
 
 }  // namespace

@@ -10,6 +10,7 @@
 //                S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T
 //   delta_head : the unpipelined variant of the dQ sweep kept in this file; it only produces
 //                delta_i = sum_j p_ij dp_ij for the first rows of every head
+// Between the kernels the row statistics travel as neg_delta = -delta and lse2 = LSE * log2(e).
 //
 // Every output element is produced by exactly one lane, so there are no atomics and the
 // result is bit-reproducible.
@@ -18,19 +19,27 @@
 
 namespace helix {
 
+constexpr int kPreprocessPasses = 4;   // rows in flight per lane group
+
 // ------------------------------------------------------------------ preprocess
-// One row of D bf16 is D/8 16-byte chunks; D/8 adjacent lanes own a row.
+// One row of D bf16 is D/8 16-byte chunks; D/8 adjacent lanes own a row.  Besides the row
+// sums the kernel rewrites LSE in the form the two gradient passes consume, so that neither
+// spends a vector instruction per score element on it:
+//   neg_delta_i = -sum_d dO_id * O_id      (becomes the initial accumulator of the dP product)
+//   lse2_i      = LSE_i * log2(e)          (P = exp2(S * scale * log2(e) - lse2))
+// Workgroup ids enumerate (slice, row block) in one dimension: no limit on B * H.
 template <int D>
 __global__ void __launch_bounds__(256)
-bwd_preprocess_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ dO,
-                      float* __restrict__ delta, TensorMap mo, TensorMap mdo, int H, int S) {
+bwd_preprocess_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ dO, const float* __restrict__ lse,
+                      float* __restrict__ neg_delta, float* __restrict__ lse2, TensorMap mo, TensorMap mdo,
+                      int H, int S, int blocks_per_head) {
   constexpr int LPR = D / 8;            // lanes per row
   constexpr int RPB = 256 / LPR;        // rows per workgroup pass
-  constexpr int PASSES = 4;
+  constexpr int PASSES = kPreprocessPasses;
   const int tid = threadIdx.x;
   const int sub = tid % LPR;
-  const int bh = blockIdx.y;
-  const int row0 = blockIdx.x * (RPB * PASSES) + tid / LPR;
+  const int bh = blockIdx.x / blocks_per_head;
+  const int row0 = (blockIdx.x - bh * blocks_per_head) * (RPB * PASSES) + tid / LPR;
   const __bf16* oh = o + head_offset(mo, bh, H);
   const __bf16* gh = dO + head_offset(mdo, bh, H);
   bf16x8 a[PASSES], b[PASSES];
@@ -38,8 +47,8 @@ bwd_preprocess_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d
   for (int p = 0; p < PASSES; p++) {
     const int r = row0 + p * RPB;
     if (r < S) {
-      a[p] = *reinterpret_cast<const bf16x8*>(oh + (size_t)r * mo.row + sub * 8);
-      b[p] = *reinterpret_cast<const bf16x8*>(gh + (size_t)r * mdo.row + sub * 8);
+      a[p] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(oh + (size_t)r * mo.row + sub * 8));
+      b[p] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(gh + (size_t)r * mdo.row + sub * 8));
     }
   }
 #pragma unroll
@@ -52,21 +61,24 @@ bwd_preprocess_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d
     }
 #pragma unroll
     for (int off = LPR / 2; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-    if (sub == 0 && r < S) delta[(size_t)bh * S + r] = s;
+    if (sub == 0 && r < S) {
+      neg_delta[(size_t)bh * S + r] = -s;
+      lse2[(size_t)bh * S + r] = lse[(size_t)bh * S + r] * kLog2e;
+    }
   }
 }
 
-hipError_t launch_bwd_preprocess(const void* o, const void* dO, float* delta, const BwdMaps& maps,
-                                 int B, int H, int S, int D, hipStream_t stream) {
-  if (D == 128) {
-    const int per = (256 / 16) * 4;
-    hipLaunchKernelGGL(bwd_preprocess_kernel<128>, dim3((unsigned)((S + per - 1) / per), (unsigned)(B * H)), dim3(256), 0,
-                       stream, (const __bf16*)o, (const __bf16*)dO, delta, maps.o, maps.dO, H, S);
-  } else {
-    const int per = (256 / 8) * 4;
-    hipLaunchKernelGGL(bwd_preprocess_kernel<64>, dim3((unsigned)((S + per - 1) / per), (unsigned)(B * H)), dim3(256), 0,
-                       stream, (const __bf16*)o, (const __bf16*)dO, delta, maps.o, maps.dO, H, S);
-  }
+hipError_t launch_bwd_preprocess(const void* o, const void* dO, const float* lse, float* neg_delta, float* lse2,
+                                 const BwdMaps& maps, int B, int H, int S, int D, hipStream_t stream) {
+  const int per = (256 / (D / 8)) * kPreprocessPasses;
+  const int bph = (S + per - 1) / per;
+  const unsigned grid = (unsigned)((long long)bph * B * H);
+  if (D == 128)
+    hipLaunchKernelGGL(bwd_preprocess_kernel<128>, dim3(grid), dim3(256), 0, stream, (const __bf16*)o, (const __bf16*)dO, lse,
+                       neg_delta, lse2, maps.o, maps.dO, H, S, bph);
+  else
+    hipLaunchKernelGGL(bwd_preprocess_kernel<64>, dim3(grid), dim3(256), 0, stream, (const __bf16*)o, (const __bf16*)dO, lse,
+                       neg_delta, lse2, maps.o, maps.dO, H, S, bph);
   return hipGetLastError();
 }
 
@@ -78,7 +90,7 @@ hipError_t launch_bwd_preprocess(const void* o, const void* dO, float* delta, co
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(512, 1)
 bwd_delta_head_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
-                      const __bf16* __restrict__ dO, const float* __restrict__ lse, float* __restrict__ delta_out,
+                      const __bf16* __restrict__ dO, const float* __restrict__ lse, float* __restrict__ neg_delta_out,
                       BwdMaps maps, int BH, int H, int S, int T, float scale) {
   constexpr int BM = 256, BN = 64, NT = 512;
   constexpr int KS = D / 16;
@@ -161,7 +173,7 @@ bwd_delta_head_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k
   }
 
   dsum = half_sum(dsum);
-  if (my_q < S && half == 0) delta_out[(size_t)tc.bh * S + my_q] = dsum;
+  if (my_q < S && half == 0) neg_delta_out[(size_t)tc.bh * S + my_q] = -dsum;
 }
 
 template <int D, bool CAUSAL>
@@ -173,7 +185,8 @@ static hipError_t launch_delta_head_t(const void* q, const void* k, const void* 
   const unsigned grid = (unsigned)grid_blocks(BH, T);
   const size_t lds = 4 * BN * D * 2;
   auto kern = bwd_delta_head_kernel<D, CAUSAL>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  static unsigned long long configured = 0;   // one static per template instantiation
+  hipError_t e = allow_dynamic_lds(kern, lds, configured);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, stream, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v,
                      (const __bf16*)dO, lse, delta_out, maps, BH, H, S, T, scale);

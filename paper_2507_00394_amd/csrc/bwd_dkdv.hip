@@ -3,8 +3,10 @@
 // Work split: a workgroup of 4 waves owns 128 keys of one (batch, head) slice, 32 keys per
 // wave, and sweeps the 64-row query tiles that see them.  Per 32-row query block b a wave
 // evaluates, with the 32x32x16 bf16 MFMA and a lane owning ONE key (column l%32):
-//     S(b)  = Q(b) K^T                P(b)  = exp2(S(b)*c - LSE*log2e)      (c = scale*log2e)
-//     dP(b) = dO(b) V^T               dS(b) = P(b) o (dP(b) - delta)
+//     S(b)  = Q(b) K^T                P(b)  = exp2(S(b)*c - lse2)           (c = scale*log2e)
+//     dP(b) = dO(b) V^T - delta       dS(b) = P(b) o dP(b)
+// (lse2 = LSE*log2e and -delta come precomputed from the preprocess kernel; -delta is the
+// initial accumulator of the dP product, so neither costs an instruction per score element)
 //     dV^T += dO(b)^T bf16(P(b))      dK^T += Q(b)^T bf16(dS(b))            (dK scaled at the end)
 // K and V fragments of the wave's keys stay in registers (B operands of S and dP); bf16(P),
 // bf16(dS) in accumulator layout are the B operands of the last two products; Q, dO come
@@ -17,11 +19,11 @@
 // stream.  The sweep is software pipelined over the blocks; a step for block b is ONE basic
 // block of 4*D/16 hand-ordered slots, each with one MFMA, the LDS read of the A operand
 // needed four slots later, and a share of the vector work:
-//     slots  0.. 7   S(b+1)           | dS(b) = P(b) o (dP(b) - delta), bf16 packs of P(b), dS(b)
+//     slots  0.. 7   S(b+1)           | dS(b) = P(b) o dP(b), bf16 packs of P(b), dS(b)
 //     slots  8..15   dP(b+1)          |   (one element per slot)
-//     slots 16..23   dV^T += ..P(b)   | P(b+1) = exp2(S(b+1)*c - LSE*log2e)
+//     slots 16..23   dV^T += ..P(b)   | P(b+1) = exp2(S(b+1)*c - lse2)
 //     slots 24..31   dK^T += ..dS(b)  |   (one element per slot)
-// Q / dO / LSE / delta tiles are copied global -> LDS asynchronously into four stages: while
+// Q / dO / lse2 / -delta tiles are copied global -> LDS asynchronously into four stages: while
 // tile t is worked on, tile t+1 (which the second step of the iteration already reads) is
 // resident too, tile t+2 may still be landing and tile t+3 is being issued; one workgroup
 // barrier per 64-row tile.  Blocks cut by the causal diagonal
@@ -47,6 +49,16 @@ __device__ __forceinline__ f32x4 lds_f32x4(uint32_t addr, int imm) {
       reinterpret_cast<const __attribute__((address_space(3))) char*>((uintptr_t)addr) + imm);
 }
 
+// Four consecutive groups of four accumulator registers as one accumulator.
+__device__ __forceinline__ f32x16 join4(const f32x4 (&x)[4]) {
+  f32x16 r;
+#pragma unroll
+  for (int g = 0; g < 4; g++)
+#pragma unroll
+    for (int e = 0; e < 4; e++) r[4 * g + e] = x[g][e];
+  return r;
+}
+
 __device__ __forceinline__ uint32_t pack_bf16_pair(float a, float b) {
   typedef float f32x2 __attribute__((ext_vector_type(2)));
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -59,7 +71,7 @@ struct Geometry {
   static constexpr int KS = D / 16, DB = D / 32;
   static constexpr int TILE = 64 * D * 2;            // one 64-row bf16 tile
   static constexpr int ROWS32 = 32 * D * 2;          // bytes of 32 rows
-  static constexpr int STATS = 2 * TILE;             // per-wave copies of LSE[64], delta[64] follow Q, dO
+  static constexpr int STATS = 2 * TILE;             // per-wave copies of lse2[64], -delta[64] follow Q, dO
   static constexpr int STAGE = 2 * TILE + 4 * 512;
   static constexpr int NSTAGE = 4;
 };
@@ -70,16 +82,16 @@ struct Pipe {
   static constexpr int KS = D / 16, DB = D / 32;
   uint32_t aq[KS];        // Q operand ks, row n of the tile that holds the block AHEAD (b+1)
   uint32_t at[DB][2];     // transposing-read addresses in the tile that holds the CURRENT block b
-  uint32_t astat;         // this wave's LSE / delta copies of the tile that holds block b+1
+  uint32_t astat;         // this wave's lse2 / -delta copies of the tile that holds block b+1
   bf16x8 ring[kRing];     // A operands of the next four slots
-  f32x4 st_dl[4];         // delta of the current block's rows 8g + 4*half + (0..3)
-  f32x4 st_l2[4];         // LSE of the block ahead, same rows
+  f32x4 st_nd[4];         // -delta of the block ahead, rows 8g + 4*half + (0..3)
+  f32x4 st_l2[4];         // lse2 of the block ahead, same rows
 };
 
 // One pipelined step for block b (see the header comment).  ODD: b is the second block of its
 // tile, so the block ahead starts the next tile.  On entry sp_cur = P(b) (fp32), dp_cur =
-// dP(b), pipe.st_dl = delta(b), pipe.ring = first Q operands of block b+1; on exit the same
-// holds for block b+1 in sp_next / dp_next.
+// dP(b) (delta already subtracted), pipe.ring = first Q operands of block b+1; on exit the
+// same holds for block b+1 in sp_next / dp_next.
 template <int D, bool ODD>
 __device__ __forceinline__ void dkdv_step(const f32x16& sp_cur, const f32x16& dp_cur, f32x16& sp_next, f32x16& dp_next,
                                           Pipe<D>& pp, const bf16x8 (&kf)[D / 16], const bf16x8 (&vf)[D / 16],
@@ -100,7 +112,7 @@ __device__ __forceinline__ void dkdv_step(const f32x16& sp_cur, const f32x16& dp
     if (s < KS) {
       sp_next = mfma32(pp.ring[s % R], kf[s], s == 0 ? zero : sp_next);
     } else if (s < 2 * KS) {
-      dp_next = mfma32(pp.ring[s % R], vf[s - KS], s == KS ? zero : dp_next);
+      dp_next = mfma32(pp.ring[s % R], vf[s - KS], s == KS ? join4(pp.st_nd) : dp_next);
     } else if (s < 3 * KS) {
       const int i = s - 2 * KS;
       const u32x4 b = {pk[4 * (i / DB)], pk[4 * (i / DB) + 1], pk[4 * (i / DB) + 2], pk[4 * (i / DB) + 3]};
@@ -134,28 +146,27 @@ __device__ __forceinline__ void dkdv_step(const f32x16& sp_cur, const f32x16& dp
         pp.ring[s % R] = lds_b128(pp.aq[u - NS], NEXT_AHEAD);
       }
     }
-    // ---- LSE / delta of the block ahead
+    // ---- lse2 / -delta of the block ahead
+    if (s < 4) pp.st_nd[s] = lds_f32x4(pp.astat, 256 + (AHEAD_ROWS + 8 * s) * 4);
     if (s >= KS && s < KS + 4) pp.st_l2[s - KS] = lds_f32x4(pp.astat, (AHEAD_ROWS + 8 * (s - KS)) * 4);
     // ---- vector work of this slot
     if (s < 2 * KS) {
-      // dS(b) = P(b) o (dP(b) - delta) and the bf16 packs of P(b), dS(b)
+      // dS(b) = P(b) o dP(b) and the bf16 packs of P(b), dS(b)
 #pragma unroll
       for (int e = 0; e < 16; e++) {
         if (e * 2 * KS / 16 != s) continue;
-        const float ds = sp_cur[e] * (dp_cur[e] - pp.st_dl[e / 4][e % 4]);
+        const float ds = sp_cur[e] * dp_cur[e];
         if (e & 1) { pk[e / 2] = pack_bf16_pair(p_prev, sp_cur[e]); sk[e / 2] = pack_bf16_pair(ds_prev, ds); }
         else { p_prev = sp_cur[e]; ds_prev = ds; }
       }
     } else {
-      // P(b+1) = exp2(S(b+1)*c - LSE*log2e), in place
+      // P(b+1) = exp2(S(b+1)*c - lse2), in place
 #pragma unroll
       for (int e = 0; e < 16; e++) {
         if (e * 2 * KS / 16 != s - 2 * KS) continue;
-        sp_next[e] = __builtin_amdgcn_exp2f(fmaf(sp_next[e], c, -(pp.st_l2[e / 4][e % 4] * kLog2e)));
+        sp_next[e] = __builtin_amdgcn_exp2f(fmaf(sp_next[e], c, -pp.st_l2[e / 4][e % 4]));
       }
     }
-    // delta of the block ahead replaces the current block's once that has been consumed
-    if (s >= 3 * KS && s < 3 * KS + 4) pp.st_dl[s - 3 * KS] = lds_f32x4(pp.astat, 256 + (AHEAD_ROWS + 8 * (s - 3 * KS)) * 4);
     __builtin_amdgcn_sched_barrier(0);
   }
   if (!ODD) pp.astat += stage_step;
@@ -166,7 +177,7 @@ __device__ __forceinline__ void dkdv_step(const f32x16& sp_cur, const f32x16& dp
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
-                const __bf16* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ delta,
+                const __bf16* __restrict__ dO, const float* __restrict__ lse2, const float* __restrict__ neg_delta,
                 __bf16* __restrict__ dk, __bf16* __restrict__ dv, BwdMaps maps, int BH, int H, int S, int T,
                 float scale) {
   using G = Geometry<D>;
@@ -185,8 +196,8 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
   const __bf16* gh = dO + head_offset(maps.dO, tc.bh, H);
   const __bf16* kh = k + head_offset(maps.k, tc.bh, H);
   const __bf16* vh = v + head_offset(maps.v, tc.bh, H);
-  const float* lse_h = lse + (size_t)tc.bh * S;
-  const float* delta_h = delta + (size_t)tc.bh * S;
+  const float* lse_h = lse2 + (size_t)tc.bh * S;
+  const float* delta_h = neg_delta + (size_t)tc.bh * S;
   const float c = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, scale * kLog2e)));
   const uint32_t base = lds_base(smem);
 
@@ -268,11 +279,11 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
       for (int e4 = 0; e4 < 4; e4++) {
         const int e = 4 * g + e4;
         const int row = r0 + 8 * g + 4 * half + e4;
-        float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], c, -(l4[e4] * kLog2e)));
+        float p = __builtin_amdgcn_exp2f(fmaf(sacc[e], c, -l4[e4]));
         const bool ok = (!CAUSAL || my_key <= row) && row < S;
         p = ok ? p : 0.f;
         sacc[e] = p;
-        pacc[e] = p * (pacc[e] - d4[e4]);
+        pacc[e] = p * (pacc[e] + d4[e4]);
       }
     }
 #pragma unroll
@@ -317,19 +328,19 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
     f32x16 spA, dpA, spB, dpB;
     {
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      spA = zero; dpA = zero;
+#pragma unroll
+      for (int g = 0; g < 4; g++) {
+        pp.st_l2[g] = lds_f32x4(pp.astat, 8 * g * 4);
+        pp.st_nd[g] = lds_f32x4(pp.astat, 256 + 8 * g * 4);
+      }
+      spA = zero; dpA = join4(pp.st_nd);
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) spA = mfma32(lds_b128(pp.aq[ks], 0), kf[ks], spA);
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) dpA = mfma32(lds_b128(pp.aq[ks], G::TILE), vf[ks], dpA);
 #pragma unroll
-      for (int g = 0; g < 4; g++) {
-        pp.st_l2[g] = lds_f32x4(pp.astat, 8 * g * 4);
-        pp.st_dl[g] = lds_f32x4(pp.astat, 256 + 8 * g * 4);
-      }
-#pragma unroll
       for (int e = 0; e < 16; e++)
-        spA[e] = __builtin_amdgcn_exp2f(fmaf(spA[e], c, -(pp.st_l2[e / 4][e % 4] * kLog2e)));
+        spA[e] = __builtin_amdgcn_exp2f(fmaf(spA[e], c, -pp.st_l2[e / 4][e % 4]));
 #pragma unroll
       for (int i = 0; i < kRing; i++) pp.ring[i] = lds_b128(pp.aq[i], G::ROWS32);
     }
@@ -362,27 +373,28 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
 
 template <int D, bool CAUSAL>
 static hipError_t launch_dkdv_t(const void* q, const void* k, const void* v, const void* dO,
-                                const float* lse, const float* delta, void* dk, void* dv, const BwdMaps& maps,
+                                const float* lse2, const float* neg_delta, void* dk, void* dv, const BwdMaps& maps,
                                 int B, int H, int S, float scale, hipStream_t stream) {
   constexpr int BN = 128;
   const int T = (S + BN - 1) / BN, BH = B * H;
   const unsigned grid = (unsigned)grid_blocks(BH, T);
   const size_t lds = Geometry<D>::NSTAGE * Geometry<D>::STAGE;
   auto kern = bwd_dkdv_kernel<D, CAUSAL>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  static unsigned long long configured = 0;   // one static per template instantiation
+  hipError_t e = allow_dynamic_lds(kern, lds, configured);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v,
-                     (const __bf16*)dO, lse, delta, (__bf16*)dk, (__bf16*)dv, maps, BH, H, S, T, scale);
+                     (const __bf16*)dO, lse2, neg_delta, (__bf16*)dk, (__bf16*)dv, maps, BH, H, S, T, scale);
   return hipGetLastError();
 }
 
 hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* dO,
-                           const float* lse, const float* delta, void* dk, void* dv, const BwdMaps& maps,
+                           const float* lse2, const float* neg_delta, void* dk, void* dv, const BwdMaps& maps,
                            int B, int H, int S, int D, float scale, bool causal, hipStream_t stream) {
-  if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, dO, lse, delta, dk, dv, maps, B, H, S, scale, stream)
-                              : launch_dkdv_t<128, false>(q, k, v, dO, lse, delta, dk, dv, maps, B, H, S, scale, stream);
-  return causal ? launch_dkdv_t<64, true>(q, k, v, dO, lse, delta, dk, dv, maps, B, H, S, scale, stream)
-                : launch_dkdv_t<64, false>(q, k, v, dO, lse, delta, dk, dv, maps, B, H, S, scale, stream);
+  if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, stream)
+                              : launch_dkdv_t<128, false>(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, stream);
+  return causal ? launch_dkdv_t<64, true>(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, stream)
+                : launch_dkdv_t<64, false>(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, stream);
 }
 
 }  // namespace helix

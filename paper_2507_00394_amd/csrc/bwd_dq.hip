@@ -4,8 +4,10 @@
 // wave, and sweeps the 64-key tiles the causal mask leaves visible.  Everything is kept
 // transposed so that a lane owns ONE query (column l%32): its LSE and delta are plain
 // per-lane scalars.  Per 32-key half tile h a wave evaluates with the 32x32x16 bf16 MFMA
-//     S^T(h)  = K(h) Q^T        P^T  = exp2(S^T*c - LSE*log2e)          (c = scale*log2e)
-//     dP^T(h) = V(h) dO^T       dS^T = P^T o (dP^T - delta)
+//     S^T(h)  = K(h) Q^T            P^T  = exp2(S^T*c - lse2)           (c = scale*log2e)
+//     dP^T(h) = V(h) dO^T - delta   dS^T = P^T o dP^T
+// (lse2 = LSE*log2e and -delta come from the preprocess kernel; -delta, replicated over an
+// accumulator, is the initial value of the dP^T product)
 //     dQ^T   += K(h)^T bf16(dS^T)                                        (dQ scaled at the end)
 // Q and dO fragments of the wave's queries stay in registers (B operands); K and V rows come
 // from LDS as A operands, K a second time through the transposing LDS read.
@@ -14,7 +16,7 @@
 // 3*D/16 hand-ordered slots per half step, each slot with one MFMA, the LDS read of the A
 // operand needed four slots later and a share of the vector work:
 //     slots  0.. 7   dP^T(h)   = V(h) dO^T      | P^T(h), second half of the exponentials
-//     slots  8..15   S^T(h+1)  = K(h+1) Q^T     | dS^T(h) = P^T o (dP^T - delta), bf16 packs
+//     slots  8..15   S^T(h+1)  = K(h+1) Q^T     | dS^T(h) = P^T o dP^T, bf16 packs
 //     slots 16..23   dQ^T     += K(h)^T dS^T(h) | P^T(h+1), first half of the exponentials
 // K / V tiles are copied global -> LDS asynchronously into four stages (tile j and j+1
 // resident, j+2 landing, j+3 being issued); one workgroup barrier per 64-key tile.  The last
@@ -44,7 +46,7 @@ template <int D, bool B_HALF>
 __device__ __forceinline__ void dq_half_step(f32x16& s_cur, f32x16& s_next, bf16x8 (&ring)[kRing],
                                              const bf16x8 (&qf)[D / 16], const bf16x8 (&gf)[D / 16],
                                              f32x16 (&dqacc)[D / 32], uint32_t (&ab)[D / 16], uint32_t (&at)[D / 32][2],
-                                             int stage_step, float c, float lse2, float dl) {
+                                             int stage_step, float c, float lse2, const f32x16& nd) {
   constexpr int KS = D / 16, DB = D / 32, NS = 3 * KS, R = kRing;
   constexpr int TILE = 64 * D * 2, HALF = 32 * D * 2;
   constexpr int V_CUR = TILE + (B_HALF ? HALF : 0);      // V rows of h, stage layout [K tile][V tile]
@@ -61,7 +63,7 @@ __device__ __forceinline__ void dq_half_step(f32x16& s_cur, f32x16& s_next, bf16
   for (int s = 0; s < NS; s++) {
     // ---- matrix work
     if (s < KS) {
-      dp = mfma32(ring[s % R], gf[s], s == 0 ? zero : dp);
+      dp = mfma32(ring[s % R], gf[s], s == 0 ? nd : dp);
     } else if (s < 2 * KS) {
       s_next = mfma32(ring[s % R], qf[s - KS], s == KS ? zero : s_next);
     } else {
@@ -98,8 +100,8 @@ __device__ __forceinline__ void dq_half_step(f32x16& s_cur, f32x16& s_next, bf16
     } else if (s < 2 * KS) {
 #pragma unroll
       for (int e = (s - KS) * ED; e < (s - KS + 1) * ED; e += 2) {
-        const float d0 = s_cur[e] * (dp[e] - dl);
-        const float d1 = s_cur[e + 1] * (dp[e + 1] - dl);
+        const float d0 = s_cur[e] * dp[e];
+        const float d1 = s_cur[e + 1] * dp[e + 1];
         sk[e / 2] = pack_pair(d0, d1);
       }
     } else {
@@ -116,7 +118,7 @@ __device__ __forceinline__ void dq_half_step(f32x16& s_cur, f32x16& s_next, bf16
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(512, 1)
 bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
-                   const __bf16* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ delta,
+                   const __bf16* __restrict__ dO, const float* __restrict__ lse2_all, const float* __restrict__ neg_delta,
                    __bf16* __restrict__ dq, BwdMaps maps, int BH, int H, int S, int T, float scale) {
   constexpr int BM = 256, BN = 64;
   constexpr int KS = D / 16, DB = D / 32;
@@ -139,7 +141,8 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
   const uint32_t base = lds_base(smem);
 
   bf16x8 qf[KS], gf[KS];
-  float lse2, dl;
+  float lse2;
+  f32x16 nd;     // -delta of this lane's query in every accumulator register
   {
     const int row = my_q < S ? my_q : S - 1;
 #pragma unroll
@@ -147,11 +150,13 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
       qf[ks] = *reinterpret_cast<const bf16x8*>(qh + (size_t)row * maps.q.row + 16 * ks + 8 * half);
       gf[ks] = *reinterpret_cast<const bf16x8*>(gh + (size_t)row * maps.dO.row + 16 * ks + 8 * half);
     }
-    lse2 = lse[(size_t)tc.bh * S + row] * kLog2e;
-    dl = delta[(size_t)tc.bh * S + row];
+    lse2 = lse2_all[(size_t)tc.bh * S + row];
+    const float dl = neg_delta[(size_t)tc.bh * S + row];
+#pragma unroll
+    for (int e = 0; e < 16; e++) nd[e] = dl;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) { pin(qf[ks]); pin(gf[ks]); }
-    pin(lse2); pin(dl);
+    pin(lse2); pin(nd);
   }
   f32x16 dqacc[DB];
 #pragma unroll
@@ -224,8 +229,8 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
   for (; j < n_w - 1; j++) {
     copy_ahead();
     const int stage_step = (st == 3) ? -3 * STAGE : STAGE;
-    dq_half_step<D, false>(sa, sb, ring, qf, gf, dqacc, ab, at, stage_step, c, lse2, dl);
-    dq_half_step<D, true>(sb, sa, ring, qf, gf, dqacc, ab, at, stage_step, c, lse2, dl);
+    dq_half_step<D, false>(sa, sb, ring, qf, gf, dqacc, ab, at, stage_step, c, lse2, nd);
+    dq_half_step<D, true>(sb, sa, ring, qf, gf, dqacc, ab, at, stage_step, c, lse2, nd);
     finish_tile();
   }
 
@@ -252,7 +257,7 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
 #pragma unroll
           for (int e = 0; e < 16; e++) sacc[e] = __builtin_amdgcn_exp2f(fmaf(sacc[e], c, -lse2));
         }
-        pacc = zero;
+        pacc = nd;
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) pacc = mfma32(lds_b128(ab[ks], TILE + kb * HALF), gf[ks], pacc);
 #pragma unroll
@@ -262,7 +267,7 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
             const int key = k0 + 32 * kb + 8 * (e >> 2) + 4 * half + (e & 3);
             p = (CAUSAL ? key <= my_q : key < S) ? p : 0.f;
           }
-          pacc[e] = p * (pacc[e] - dl);
+          pacc[e] = p * pacc[e];
         }
 #pragma unroll
         for (int t = 0; t < 2; t++) {
@@ -292,27 +297,28 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
 
 template <int D, bool CAUSAL>
 static hipError_t launch_dq_pipe_t(const void* q, const void* k, const void* v, const void* dO,
-                                   const float* lse, const float* delta, void* dq, const BwdMaps& maps,
+                                   const float* lse2, const float* neg_delta, void* dq, const BwdMaps& maps,
                                    int B, int H, int S, float scale, hipStream_t stream) {
   constexpr int BM = 256, BN = 64;
   const int T = (S + BM - 1) / BM, BH = B * H;
   const unsigned grid = (unsigned)grid_blocks(BH, T);
   const size_t lds = 4 * 2 * BN * D * 2;
   auto kern = bwd_dq_pipe_kernel<D, CAUSAL>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  static unsigned long long configured = 0;   // one static per template instantiation
+  hipError_t e = allow_dynamic_lds(kern, lds, configured);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, stream, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v,
-                     (const __bf16*)dO, lse, delta, (__bf16*)dq, maps, BH, H, S, T, scale);
+                     (const __bf16*)dO, lse2, neg_delta, (__bf16*)dq, maps, BH, H, S, T, scale);
   return hipGetLastError();
 }
 
 hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void* dO,
-                         const float* lse, const float* delta, void* dq, const BwdMaps& maps,
+                         const float* lse2, const float* neg_delta, void* dq, const BwdMaps& maps,
                          int B, int H, int S, int D, float scale, bool causal, hipStream_t stream) {
-  if (D == 128) return causal ? launch_dq_pipe_t<128, true>(q, k, v, dO, lse, delta, dq, maps, B, H, S, scale, stream)
-                              : launch_dq_pipe_t<128, false>(q, k, v, dO, lse, delta, dq, maps, B, H, S, scale, stream);
-  return causal ? launch_dq_pipe_t<64, true>(q, k, v, dO, lse, delta, dq, maps, B, H, S, scale, stream)
-                : launch_dq_pipe_t<64, false>(q, k, v, dO, lse, delta, dq, maps, B, H, S, scale, stream);
+  if (D == 128) return causal ? launch_dq_pipe_t<128, true>(q, k, v, dO, lse2, neg_delta, dq, maps, B, H, S, scale, stream)
+                              : launch_dq_pipe_t<128, false>(q, k, v, dO, lse2, neg_delta, dq, maps, B, H, S, scale, stream);
+  return causal ? launch_dq_pipe_t<64, true>(q, k, v, dO, lse2, neg_delta, dq, maps, B, H, S, scale, stream)
+                : launch_dq_pipe_t<64, false>(q, k, v, dO, lse2, neg_delta, dq, maps, B, H, S, scale, stream);
 }
 
 }  // namespace helix

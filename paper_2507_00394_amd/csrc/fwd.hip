@@ -372,7 +372,8 @@ static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, void
   const unsigned grid = (unsigned)grid_blocks(BH, T);
   const size_t lds = 8 * BN * D * 2;
   auto kern = fwd_kernel<D, CAUSAL>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  static unsigned long long configured = 0;   // one static per template instantiation
+  hipError_t e = allow_dynamic_lds(kern, lds, configured);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, stream, (const __bf16*)q, (const __bf16*)k,
                      (const __bf16*)v, (__bf16*)o, lse, maps, BH, H, S, T, scale);

@@ -100,6 +100,10 @@ struct TileStage {
 // that any later LDS read may alias the copy and waits for it at once, which would serialise
 // the copy of the next tile with the work on the current one.  The caller waits
 // (`wait_tile_loads*`) and then barriers before anyone reads the tile.
+// The statements write M0 without declaring it: M0 is not an allocatable register (the
+// compiler rejects it in a clobber list as reserved) and the compiler itself only loads it
+// immediately in front of its own users (sendmsg, movrel, its LDS-copy builtins), none of
+// which these kernels contain; no value of the compiler's ever lives in M0 across them.
 // A pointer the caller knows to be wave-uniform, moved into scalar registers.
 template <typename T>
 __device__ __forceinline__ const T* uniform_ptr(const T* p) {

@@ -15,22 +15,38 @@ inline TensorMap contiguous_map(int H, int S, int D) {
   return TensorMap{(long long)H * S * D, (long long)S * D, D};
 }
 struct FwdMaps { TensorMap q, k, v, o; };
+
+// Raises a kernel's dynamic LDS limit once per device and process instead of on every launch
+// (the attribute call costs as much as a small launch).  `done` is the caller's per-kernel
+// bit mask of devices already configured.
+template <typename Kernel>
+inline hipError_t allow_dynamic_lds(Kernel kern, size_t bytes, unsigned long long& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (__atomic_load_n(&done, __ATOMIC_ACQUIRE) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) __atomic_fetch_or(&done, bit, __ATOMIC_RELEASE);
+  return e;
+}
 struct BwdMaps { TensorMap q, k, v, o, dO, dq, dk, dv; };
 
-// lse, delta and every other per-row fp32 array are contiguous [B, H, S].
+// lse and every other per-row fp32 array are contiguous [B, H, S].  Between the backward
+// kernels the row statistics travel as neg_delta = -rowsum(dO o O) and lse2 = lse * log2(e).
 hipError_t launch_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const FwdMaps& maps,
                       int B, int H, int S, int D, float scale, bool causal, hipStream_t stream);
-hipError_t launch_bwd_preprocess(const void* o, const void* dO, float* delta, const BwdMaps& maps,
-                                 int B, int H, int S, int D, hipStream_t stream);
-// delta_i = sum_j p_ij dp_ij for query rows 0..rows-1 of every head, overwriting delta there.
+hipError_t launch_bwd_preprocess(const void* o, const void* dO, const float* lse, float* neg_delta, float* lse2,
+                                 const BwdMaps& maps, int B, int H, int S, int D, hipStream_t stream);
+// neg_delta_i = -sum_j p_ij dp_ij for query rows 0..rows-1 of every head, overwriting neg_delta there.
 hipError_t launch_bwd_delta_head(const void* q, const void* k, const void* v, const void* dO,
-                                 const float* lse, float* delta, const BwdMaps& maps, int B, int H, int S, int D,
+                                 const float* lse, float* neg_delta, const BwdMaps& maps, int B, int H, int S, int D,
                                  int rows, float scale, bool causal, hipStream_t stream);
 hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* dO,
-                           const float* lse, const float* delta, void* dk, void* dv, const BwdMaps& maps,
+                           const float* lse2, const float* neg_delta, void* dk, void* dv, const BwdMaps& maps,
                            int B, int H, int S, int D, float scale, bool causal, hipStream_t stream);
 hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void* dO,
-                         const float* lse, const float* delta, void* dq, const BwdMaps& maps,
+                         const float* lse2, const float* neg_delta, void* dq, const BwdMaps& maps,
                          int B, int H, int S, int D, float scale, bool causal, hipStream_t stream);
 
 // Linear layer next to attention: out[M][N] = a[M][K] w[K][N] (bf16, fp32 accumulation) and its

@@ -226,7 +226,8 @@ static hipError_t launch_gemm(const void* X, long long ldx, const void* Y, long 
   const unsigned grid = 8u * ((tiles_i + 7) / 8) * tiles_j;
   const size_t lds = (size_t)kStages * kStage;
   auto kern = gemm_kernel<XR, YR, OutT>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  static unsigned long long configured = 0;   // one static per template instantiation
+  hipError_t e = allow_dynamic_lds(kern, lds, configured);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid, (unsigned)parts), dim3(64 * kWaves), lds, stream, (const __bf16*)X, ldx, (const __bf16*)Y, ldy,
                      (OutT*)C, ldc, I, J, R, tiles_i, tiles_j, r_per_part, part_stride);

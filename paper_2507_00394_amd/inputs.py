@@ -119,10 +119,19 @@ def sample_rows(cfg: AttnConfig, n: int = 256, seed: int = 7):
     return picks[:n]
 
 
-def sample_cols(cfg: AttnConfig, n_full: int = 64, n_tail: int = 128, tail: int = 1024, tail_heads: int = 16, seed: int = 11):
-    """Key-column sample: ``full`` = {bh: [j...]} over the whole range for the first and last
-    head (tile edges forced), ``tail`` = {bh: [j...]} with j in the last ``tail`` positions of
-    up to ``tail_heads`` randomly drawn heads (``n_tail`` draws in total)."""
+TAIL_WINDOW = 4096   # the tail stratum of the key-column sample lies in the last TAIL_WINDOW positions
+
+
+def sample_cols(cfg: AttnConfig, n_full: int = 64, n_tail: int = 128, n_mid: int = 16, tail: int = TAIL_WINDOW, seed: int = 11):
+    """Key-column sample in three strata, each a dict {bh: [j...]}:
+
+    ``full``  whole key range of the first and the last (batch, head) slice, tile edges forced
+              (a column needs the statistics of every later row: a whole forward of the head);
+    ``mid``   columns of the second half of the sequence, before the tail window, in the middle
+              slice (needs the rows from S/2 on);
+    ``tail``  ``n_tail`` draws in the last ``tail`` positions dealt round-robin over ALL other
+              slices, so that every head's last tiles are compared (needs the last rows only).
+    """
     S, BH = cfg.S, cfg.B * cfg.H
     rng = np.random.Generator(np.random.Philox(key=np.array([SEED, (seed << 32) | cfg.cfg_id], dtype=np.uint64)))
     forced = sorted({j for j in [0, 1, 127, 128, 255, 256, S // 2, S - 128, S - 1] if 0 <= j < S})
@@ -133,11 +142,17 @@ def sample_cols(cfg: AttnConfig, n_full: int = 64, n_tail: int = 128, tail: int 
             cols.append(int(rng.integers(S)))
         full[bh] = sorted(set(cols))
     lo = max(0, S - tail)
-    heads = sorted({int(rng.integers(BH)) for _ in range(tail_heads)})
-    tail_cols = {bh: set() for bh in heads}
-    for _ in range(n_tail):
-        tail_cols[heads[int(rng.integers(len(heads)))]].add(int(rng.integers(lo, S)))
-    return full, {bh: sorted(c) for bh, c in tail_cols.items() if c}
+    mid = {}
+    if S // 2 < lo and BH > 2:
+        cols = {S // 2, S // 2 + 127, (S // 2 + lo) // 2, lo - 1}
+        while len(cols) < n_mid:
+            cols.add(int(rng.integers(S // 2, lo)))
+        mid[BH // 2] = sorted(cols)
+    others = [bh for bh in range(BH) if bh not in full] or list(full)
+    tail_cols = {bh: set() for bh in others}
+    for n in range(max(n_tail, len(others))):
+        tail_cols[others[n % len(others)]].add(int(rng.integers(lo, S)))
+    return full, mid, {bh: sorted(c) for bh, c in tail_cols.items() if c}
 
 
 def linear_case_bits(seed: int, M: int, K: int, N: int, w_std: float = 0.02):

@@ -31,12 +31,12 @@ def run_fwd_bwd(bits, scale, causal=True, fused_bwd=True):
         ws = torch.empty(hx.helix_attn_bwd_workspace_bytes(B, H, S, D), dtype=torch.uint8, device="cuda")
         hx.helix_attn_bwd(q, k, v, o, lse, g, dq, dk, dv, ws, scale, causal)
     else:
-        delta = torch.empty_like(lse)
-        hx.helix_attn_bwd_preprocess(o, g, delta)
+        stats = torch.empty(hx.helix_attn_bwd_workspace_bytes(B, H, S, D), dtype=torch.uint8, device="cuda")
+        hx.helix_attn_bwd_preprocess(o, g, lse, stats)
         if causal:
-            hx.helix_attn_bwd_delta_head(q, k, v, g, lse, delta, hx.DELTA_HEAD_ROWS, scale, causal)
-        hx.helix_attn_bwd_dkdv(q, k, v, g, lse, delta, dk, dv, scale, causal)
-        hx.helix_attn_bwd_dq(q, k, v, g, lse, delta, dq, scale, causal)
+            hx.helix_attn_bwd_delta_head(q, k, v, g, lse, stats, hx.DELTA_HEAD_ROWS, scale, causal)
+        hx.helix_attn_bwd_dkdv(q, k, v, g, stats, dk, dv, scale, causal)
+        hx.helix_attn_bwd_dq(q, k, v, g, stats, dq, scale, causal)
     torch.cuda.synchronize()
     return {"q": q, "k": k, "v": v, "dO": g, "o": o, "lse": lse, "dq": dq, "dk": dk, "dv": dv}
 

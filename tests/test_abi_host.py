@@ -40,9 +40,10 @@ def test_version_and_status_strings(L):
 
 
 def test_workspace_bytes(L):
-    assert hx.helix_attn_bwd_workspace_bytes(1, 2, 512, 64) == 4096
-    assert hx.helix_attn_bwd_workspace_bytes(1, 1, 1, 64) == 256
-    assert hx.helix_attn_bwd_workspace_bytes(1, 32, 131072, 128) == 32 * 131072 * 4
+    # two fp32 planes [B, H, S] (-delta and lse * log2(e)), each padded to 256 bytes
+    assert hx.helix_attn_bwd_workspace_bytes(1, 2, 512, 64) == 2 * 4096
+    assert hx.helix_attn_bwd_workspace_bytes(1, 1, 1, 64) == 2 * 256
+    assert hx.helix_attn_bwd_workspace_bytes(1, 32, 131072, 128) == 2 * 32 * 131072 * 4
     assert hx.helix_attn_bwd_workspace_bytes(1, 1, 10, 96) == 0
     assert hx.helix_attn_bwd_workspace_bytes(0, 1, 10, 64) == 0
 
@@ -64,10 +65,15 @@ def test_validation_precedes_any_device_work(L):
     assert bwd(ws=ctypes.c_void_p(0x10010)) == 4
     assert bwd(wsb=4095) == 6
     assert bwd(D=32) == 3 and bwd(scale=0.0) == 5
-    assert L.helix_attn_bwd_preprocess(p, None, p, 1, 1, 8, 64, None) == 1
+    assert bwd(wsb=2 * 4096 - 1) == 6 and bwd(wsb=2 * 4096) != 6     # two fp32 planes of B*H*S rows
+    assert L.helix_attn_bwd_workspace_bytes(1, 2, 512, 64) == 2 * 4096
+    assert L.helix_attn_bwd_workspace_bytes(1, 1, 3, 64) == 2 * 256  # each plane padded to 256 bytes
+    assert L.helix_attn_bwd_preprocess(p, None, p, p, 1, 1, 8, 64, None) == 1
+    assert L.helix_attn_bwd_preprocess(p, p, p, ctypes.c_void_p(0x10010), 1, 1, 8, 64, None) == 4   # stats need 256 bytes
     assert L.helix_attn_bwd_delta_head(p, p, p, p, p, p, -1, 1, 1, 8, 64, 0.1, 1, None) == 2
-    assert L.helix_attn_bwd_dkdv(p, p, p, p, p, p, p, odd, 1, 1, 8, 64, 0.1, 1, None) == 4
-    assert L.helix_attn_bwd_dq(p, p, p, p, p, p, p, 1, 1, 8, 128, -0.1, 1, None) == 5
+    assert L.helix_attn_bwd_dkdv(p, p, p, p, p, p, odd, 1, 1, 8, 64, 0.1, 1, None) == 4
+    assert L.helix_attn_bwd_dkdv(p, p, p, p, None, p, p, 1, 1, 8, 64, 0.1, 1, None) == 1
+    assert L.helix_attn_bwd_dq(p, p, p, p, p, p, 1, 1, 8, 128, -0.1, 1, None) == 5
 
 
 def test_stride_validation(L):

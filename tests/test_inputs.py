@@ -42,8 +42,15 @@ def test_samples_are_stratified_and_in_range():
         assert len(rows) == 256 and all(0 <= bh < cfg.B * cfg.H and 0 <= i < cfg.S for bh, i in rows)
         got = {i for _, i in rows}
         assert {0, 1, 127, 128, cfg.S // 2, cfg.S - 1} <= got
-        full, tail = I.sample_cols(cfg)
-        assert set(full) == {0, cfg.B * cfg.H - 1}
+        full, mid, tail = I.sample_cols(cfg)
+        BH = cfg.B * cfg.H
+        assert set(full) == {0, BH - 1}
         assert all({0, 1, 127, 128, cfg.S - 1} <= set(c) for c in full.values())
-        assert 100 <= sum(len(c) for c in tail.values()) <= 128 and all(cfg.S - 1024 <= j < cfg.S for c in tail.values() for j in c)
+        # the tail stratum reaches EVERY other (batch, head) slice, inside the last 4096 positions
+        assert set(tail) == set(range(1, BH - 1))
+        assert 120 <= sum(len(c) for c in tail.values()) <= 128 and all(cfg.S - 4096 <= j < cfg.S for c in tail.values() for j in c)
+        # mid-range columns of a middle slice
+        assert set(mid) == {BH // 2} and len(mid[BH // 2]) == 16
+        assert all(cfg.S // 2 <= j < cfg.S - 4096 for j in mid[BH // 2])
+        assert (full, mid, tail) == I.sample_cols(cfg)
         assert rows == I.sample_rows(cfg)

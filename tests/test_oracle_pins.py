@@ -169,6 +169,56 @@ def test_sampled_rows_and_columns_agree_with_full():
         A.head_cols(q, k, v, g, [100], lse_t, delta_t, scale, row_start=200)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_batched_forward_against_scalar_loops_per_slice(brute, causal):
+    """attn_fwd_ref on a [B, H, S, D] batch with B != H and every slice different: each slice must
+    equal the scalar-loop result of ITS OWN (b, h) inputs; an implementation that swapped the
+    batch and head index (or reused one slice) cannot pass, which the last assertion shows."""
+    B, H, S, D, scale = 2, 3, 11, 4, 0.6
+    q, k, v = (rnd(500 + t, B, H, S, D) for t in range(3))
+    o, lse = A.attn_fwd_ref(q, k, v, scale, causal)
+    assert o.shape == (B, H, S, D) and lse.shape == (B, H, S)
+    for b in range(B):
+        for h in range(H):
+            ob, lb = brute.head_forward(q[b, h], k[b, h], v[b, h], scale, causal)
+            assert np.abs(o[b, h] - ob).max() <= 1e-12 and np.abs(lse[b, h] - lb).max() <= 1e-12, (b, h)
+    # the same call on inputs with batch and head exchanged gives the exchanged result, and that
+    # differs from the original wherever (b, h) != (h, b) in flat order: slices are not interchangeable
+    ot, _ = A.attn_fwd_ref(*(x.swapaxes(0, 1).copy() for x in (q, k, v)), scale, causal)
+    assert np.array_equal(ot.swapaxes(0, 1), o)
+    assert not np.allclose(o.reshape(B * H, S, D), ot.reshape(B * H, S, D))
+    # and the backward wrapper reports the same forward
+    rb = A.attn_bwd_ref(q, k, v, rnd(503, B, H, S, D), scale, causal)
+    assert np.array_equal(rb["o"], o) and np.array_equal(rb["lse"], lse)
+
+
+def test_sampled_rows_and_columns_noncausal(brute):
+    """head_rows / head_stats / head_cols with causal=False: every row sees every key.  Pinned
+    against the full non-causal result and, independently, against the scalar loops."""
+    S, D, scale = 37, 8, 0.35
+    q, k, v, g = (rnd(600 + t, S, D) for t in range(4))
+    r = A.head_backward(q, k, v, g, scale, causal=False, row_block=16)
+    dq_b, dk_b, dv_b = brute.head_backward(q, k, v, g, scale, False)
+    o_b, lse_b = brute.head_forward(q, k, v, scale, False)
+    rows = [0, 1, 17, 36]
+    o, lse, dq = A.head_rows(q, k, v, g, rows, scale, causal=False)
+    assert np.abs(o - r["o"][rows]).max() <= 1e-13 and np.abs(lse - r["lse"][rows]).max() <= 1e-13
+    assert np.abs(dq - r["dq"][rows]).max() <= 1e-13
+    assert np.abs(o - o_b[rows]).max() <= 1e-12 and np.abs(lse - lse_b[rows]).max() <= 1e-12 and np.abs(dq - dq_b[rows]).max() <= 1e-12
+    lse_f, delta_f = A.head_stats(q, k, v, g, scale, causal=False)
+    assert np.abs(lse_f - lse_b).max() <= 1e-12
+    cols = [0, 5, 36]
+    dk, dv = A.head_cols(q, k, v, g, cols, lse_f, delta_f, scale, causal=False, row_block=10)
+    assert np.abs(dk - r["dk"][cols]).max() <= 1e-13 and np.abs(dv - r["dv"][cols]).max() <= 1e-13
+    assert np.abs(dk - dk_b[cols]).max() <= 1e-12 and np.abs(dv - dv_b[cols]).max() <= 1e-12
+    # the causal result is a different one: the flag is not ignored
+    dkc, _ = A.head_cols(q, k, v, g, cols, *A.head_stats(q, k, v, g, scale, causal=True), scale, causal=True)
+    assert not np.allclose(dkc, dk)
+    # a row window is refused without the causal mask (column j needs every row)
+    with pytest.raises(ValueError):
+        A.head_cols(q, k, v, g, [20], lse_f[10:], delta_f[10:], scale, causal=False, row_start=10)
+
+
 def test_flop_counter_matches_table1():
     for line in (GOLDEN / "table1_attention_flops.txt").read_text().splitlines():
         if line.startswith("#") or not line.strip():
