@@ -47,7 +47,8 @@ typedef enum {
   HELIX_ERR_BAD_SCALE = 5,
   HELIX_ERR_WORKSPACE = 6,
   HELIX_ERR_LAUNCH = 7,
-  HELIX_ERR_BAD_STRIDE = 8
+  HELIX_ERR_BAD_STRIDE = 8,
+  HELIX_ERR_SCRATCH_LIMIT = 9
 } helix_status;
 
 /* Element strides of a logical [B, H, S, D] bf16 tensor whose D elements per row are
@@ -88,6 +89,21 @@ int helix_attn_bwd(const void* q, const void* k, const void* v, const void* o, c
                    const void* dO, void* dq, void* dk, void* dv,
                    void* workspace, size_t workspace_bytes,
                    int B, int H, int S, int D, float scale, int causal, void* stream);
+
+/* helix_attn_bwd for callers that cannot allocate device memory -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc: the same kernels, with the
+ * row statistics kept in a device array built into the library (HELIX_STATIC_SCRATCH_BYTES
+ * = 32 MiB per GPU, held from the first call on that GPU until the process ends) instead of
+ * a caller-provided workspace.  The call itself allocates and frees nothing.  Shapes whose
+ * statistics do not fit (B*H*S > 4194304 rows, i.e. helix_attn_bwd_workspace_bytes >
+ * HELIX_STATIC_SCRATCH_BYTES) return HELIX_ERR_SCRATCH_LIMIT and enqueue nothing.  All calls
+ * on one GPU share the array: calls that may overlap in time (different streams) race; every
+ * call overwrites the part it uses before reading it, so nothing needs clearing in between.
+ * Otherwise same arguments, results (bit for bit) and error behaviour as helix_attn_bwd. */
+#define HELIX_STATIC_SCRATCH_BYTES (32u << 20)
+int helix_attn_bwd_static(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                          const void* dO, void* dq, void* dk, void* dv,
+                          int B, int H, int S, int D, float scale, int causal, void* stream);
 
 /* Bytes of scratch helix_attn_bwd needs: two fp32 planes [B, H, S], each rounded up to 256
  * bytes.  Returns 0 for an invalid shape.  Pure host arithmetic. */

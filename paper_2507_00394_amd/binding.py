@@ -13,7 +13,7 @@ import pathlib
 import torch
 
 LIB_PATH = pathlib.Path(__file__).resolve().parent / "csrc" / "libhelix_attn.so"
-EXPORTS = ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_fwd_strided", "helix_attn_bwd_strided",
+EXPORTS = ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_bwd_static", "helix_attn_fwd_strided", "helix_attn_bwd_strided",
            "helix_attn_check_strides", "helix_qkv_linear_fwd", "helix_qkv_linear_bwd", "helix_qkv_linear_bwd_workspace_bytes",
            "helix_attn_bwd_workspace_bytes",
            "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head", "helix_attn_bwd_dkdv", "helix_attn_bwd_dq",
@@ -46,6 +46,8 @@ def lib() -> ctypes.CDLL:
         vp, fp, i, f, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
         L.helix_attn_fwd.argtypes = [vp, vp, vp, vp, fp, i, i, i, i, f, i, vp]
         L.helix_attn_bwd.argtypes = [vp, vp, vp, vp, fp, vp, vp, vp, vp, vp, sz, i, i, i, i, f, i, vp]
+        L.helix_attn_bwd_static.argtypes = [vp, vp, vp, vp, fp, vp, vp, vp, vp, i, i, i, i, f, i, vp]
+        L.helix_attn_bwd_static.restype = i
         sp = ctypes.POINTER(helix_strides)
         L.helix_attn_fwd_strided.argtypes = [vp, sp, vp, sp, vp, sp, vp, sp, fp, i, i, i, i, f, i, vp]
         L.helix_attn_bwd_strided.argtypes = [vp, sp, vp, sp, vp, sp, vp, sp, fp, vp, sp, vp, sp, vp, sp, vp, sp,
@@ -143,6 +145,16 @@ def helix_attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, workspace, scale, causal=Tru
     _raise(lib().helix_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO), _ptr(dq), _ptr(dk), _ptr(dv),
                                 _ptr(workspace), workspace.numel(), B, H, S, D, float(scale), int(causal),
                                 _stream(stream)), "helix_attn_bwd")
+
+
+def helix_attn_bwd_static(q, k, v, o, lse, dO, dq, dk, dv, scale, causal=True, stream=None):
+    """helix_attn_bwd without a workspace argument: the statistics live in the library's built-in device array."""
+    B, H, S, D = q.shape
+    for n, t in (("q", q), ("k", k), ("v", v), ("o", o), ("dO", dO), ("dq", dq), ("dk", dk), ("dv", dv)):
+        _check_bf16(n, t, (B, H, S, D))
+    _check_f32("lse", lse, (B, H, S))
+    _raise(lib().helix_attn_bwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO), _ptr(dq), _ptr(dk), _ptr(dv),
+                                       B, H, S, D, float(scale), int(causal), _stream(stream)), "helix_attn_bwd_static")
 
 
 def _view(name, t, shape):

@@ -7,9 +7,16 @@
 #include <cmath>
 #include <cstdint>
 #include <initializer_list>
+#include <mutex>
 #include <utility>
 
 namespace {
+
+// Statistics planes of helix_attn_bwd_static: device memory that exists once per GPU for the
+// life of the process, so that the call allocates nothing.  In host code the array's name is
+// only a handle: the per-device address comes from hipGetSymbolAddress (scratch_base below).
+constexpr size_t kScratchBytes = HELIX_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 constexpr int kVersion = 200;  // 0.2.0
 
@@ -103,6 +110,22 @@ int check_linear(int M, int K, int N, bool need_m32, std::initializer_list<std::
 }
 
 int launched(hipError_t e) { return e == hipSuccess ? HELIX_OK : HELIX_ERR_LAUNCH; }
+
+// Address of `scratch` on the current device, looked up once per device.
+void* scratch_base() {
+  constexpr int kMaxDevices = 64;
+  static void* base[kMaxDevices] = {};
+  static std::mutex lock;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> guard(lock);
+  if (!base[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    base[dev] = p;
+  }
+  return base[dev];
+}
 
 #define HELIX_TRY(expr) do { int st_ = (expr); if (st_ != HELIX_OK) return st_; } while (0)
 
@@ -204,6 +227,20 @@ int helix_attn_bwd(const void* q, const void* k, const void* v, const void* o, c
                  B, H, S, D, scale, causal, (hipStream_t)stream);
 }
 
+int helix_attn_bwd_static(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                          const void* dO, void* dq, void* dk, void* dv,
+                          int B, int H, int S, int D, float scale, int causal, void* stream) {
+  HELIX_TRY(check_bf16_ptrs(q, k, v, o, dO, (const void*)dq, (const void*)dk, (const void*)dv));
+  HELIX_TRY(check_f32_ptrs((const void*)lse));
+  HELIX_TRY(check_shape(B, H, S, D));
+  HELIX_TRY(check_scale(scale));
+  if (helix_attn_bwd_workspace_bytes(B, H, S, D) > kScratchBytes) return HELIX_ERR_SCRATCH_LIMIT;
+  void* stats = scratch_base();
+  if (!stats) return HELIX_ERR_LAUNCH;
+  return run_bwd(q, k, v, o, lse, dO, dq, dk, dv, stats, contiguous_bwd(H, S, D), B, H, S, D, scale, causal,
+                 (hipStream_t)stream);
+}
+
 int helix_attn_bwd_strided(const void* q, const helix_strides* q_strides, const void* k, const helix_strides* k_strides,
                            const void* v, const helix_strides* v_strides, const void* o, const helix_strides* o_strides,
                            const float* lse, const void* dO, const helix_strides* dO_strides,
@@ -277,6 +314,7 @@ const char* helix_status_string(int status) {
     case HELIX_ERR_BAD_SCALE: return "bad scale: must be finite and > 0";
     case HELIX_ERR_WORKSPACE: return "workspace too small";
     case HELIX_ERR_LAUNCH: return "kernel launch failed";
+    case HELIX_ERR_SCRATCH_LIMIT: return "shape too large for the built-in scratch of helix_attn_bwd_static: B*H*S must not exceed 4194304";
     case HELIX_ERR_BAD_STRIDE: return "bad strides: multiples of 8 elements, row stride at least the row length and within the index limits, dimensions nested without overlap";
     default: return "unknown status";
   }

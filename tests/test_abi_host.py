@@ -35,8 +35,8 @@ def test_every_declared_symbol_is_exported(L):
 
 def test_version_and_status_strings(L):
     assert L.helix_attn_version() >= 100
-    seen = {hx.status_string(s) for s in range(9)}
-    assert len(seen) == 9 and hx.status_string(0) == "ok" and hx.status_string(99) == "unknown status"
+    seen = {hx.status_string(s) for s in range(10)}
+    assert len(seen) == 10 and hx.status_string(0) == "ok" and hx.status_string(99) == "unknown status"
 
 
 def test_workspace_bytes(L):
@@ -65,6 +65,12 @@ def test_validation_precedes_any_device_work(L):
     assert bwd(ws=ctypes.c_void_p(0x10010)) == 4
     assert bwd(wsb=4095) == 6
     assert bwd(D=32) == 3 and bwd(scale=0.0) == 5
+    # the allocation-free variant validates the same way and refuses shapes beyond its built-in scratch
+    static = lambda **kw: L.helix_attn_bwd_static(p, p, p, p, p, kw.get("dO", p), p, p, kw.get("dv", p), kw.get("B", 1), kw.get("H", 2),
+                                                  kw.get("S", 512), kw.get("D", 64), kw.get("scale", 0.1), 1, None)
+    assert static(dO=None) == 1 and static(dv=odd) == 4 and static(D=32) == 3 and static(scale=0.0) == 5 and static(S=0) == 2
+    assert static(B=1, H=32, S=131072 + 64, D=128) == 9 and static(B=2, H=40, S=65536, D=128) == 9
+    assert "4194304" in hx.status_string(9)
     assert bwd(wsb=2 * 4096 - 1) == 6 and bwd(wsb=2 * 4096) != 6     # two fp32 planes of B*H*S rows
     assert L.helix_attn_bwd_workspace_bytes(1, 2, 512, 64) == 2 * 4096
     assert L.helix_attn_bwd_workspace_bytes(1, 1, 3, 64) == 2 * 256  # each plane padded to 256 bytes
