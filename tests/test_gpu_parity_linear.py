@@ -76,6 +76,66 @@ def test_padded_leading_dimensions_and_untouched_padding():
     assert torch.isnan(out_buf[:, :64]).all() and torch.isnan(out_buf[:, 64 + N:]).all()
 
 
+def test_backward_padded_leading_dimensions_and_untouched_padding():
+    """da and dw written into the middle of wider buffers (padded ldda / lddw), a and dqkv read from padded ones."""
+    from paper_2507_00394_amd import binding as hx
+    from tests import gpu_util as G
+
+    M, K, N = 2080, 384, 640            # dw is split over several token ranges at this M
+    bits = I.linear_case_bits(98, M, K, N)
+    a_buf = torch.zeros(M, K + 8, dtype=torch.bfloat16, device="cuda"); a = a_buf[:, :K]; a.copy_(G.to_dev(bits["a"]))
+    g_buf = torch.zeros(M, N + 24, dtype=torch.bfloat16, device="cuda"); g = g_buf[:, 16:16 + N]; g.copy_(G.to_dev(bits["dqkv"]))
+    w = G.to_dev(bits["w"])
+    da_buf = torch.full((M, K + 128), float("nan"), dtype=torch.bfloat16, device="cuda"); da = da_buf[:, 64:64 + K]
+    dw_buf = torch.full((K, N + 72), float("nan"), dtype=torch.float32, device="cuda"); dw = dw_buf[:, 8:8 + N]
+    ws = torch.empty(hx.helix_qkv_linear_bwd_workspace_bytes(M, K, N), dtype=torch.uint8, device="cuda")
+    hx.helix_qkv_linear_bwd(a, w, g, da, dw, ws)
+    torch.cuda.synchronize()
+    f = {t: I.bf16_bits_to_float(bits[t]) for t in bits}
+    ref = L.linear_bwd_ref(f["a"], f["w"], f["dqkv"])
+    _check_bf16("da", G.to_f64(da.contiguous()), ref["da"])
+    _check_f32("dw", G.to_f64(dw.contiguous()), ref["dw"])
+    assert torch.isnan(da_buf[:, :64]).all() and torch.isnan(da_buf[:, 64 + K:]).all()
+    assert torch.isnan(dw_buf[:, :8]).all() and torch.isnan(dw_buf[:, 8 + N:]).all()
+
+
+def test_benchmark_shape_sampled():
+    """The shape `bench.py --qkv-linear` times (one GPU's share of the 7B layer at 128k tokens: M = 131072,
+    K = 4096, N = 1536; 1 GiB operands, a weight gradient split over token ranges): 256 sampled
+    elements of each of qkv, da and dw against the oracle's products of the corresponding rows / columns."""
+    from paper_2507_00394_amd import binding as hx
+    from tests import gpu_util as G
+
+    M, K, N, n = 131072, 4096, 1536, 256
+    bits = I.linear_case_bits(4242, M, K, N)
+    a, w, g = G.to_dev(bits["a"]), G.to_dev(bits["w"]), G.to_dev(bits["dqkv"])
+    qkv = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    da = torch.full((M, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dw = torch.full((K, N), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(hx.helix_qkv_linear_bwd_workspace_bytes(M, K, N), dtype=torch.uint8, device="cuda")
+    hx.helix_qkv_linear_fwd(a, w, qkv)
+    hx.helix_qkv_linear_bwd(a, w, g, da, dw, ws)
+    torch.cuda.synchronize()
+    for t in (qkv, da, dw):
+        assert bool(torch.isfinite(t.float()).all())
+    rng = np.random.Generator(np.random.Philox(key=[I.SEED, 4242]))
+    edge = lambda hi: np.array([0, 1, 255, 256, hi // 2, hi - 257, hi - 256, hi - 1])
+    ms = np.concatenate([edge(M), rng.integers(0, M, n - 8)]); ks = np.concatenate([edge(K), rng.integers(0, K, n - 8)])
+    ns = np.concatenate([edge(N), rng.integers(0, N, n - 8)])
+    rng.shuffle(ks); rng.shuffle(ns)
+    wf = I.bf16_bits_to_float(bits["w"])
+    a_rows, g_rows = I.bf16_bits_to_float(bits["a"][ms]), I.bf16_bits_to_float(bits["dqkv"][ms])
+    ref_qkv = np.diagonal(L.linear_fwd_ref(a_rows, wf[:, ns]))                       # qkv[ms[i], ns[i]]
+    ref_da = np.diagonal(L.linear_bwd_ref(a_rows[:, ks], wf[ks], g_rows)["da"])      # da[ms[i], ks[i]]
+    a_cols, g_cols = I.bf16_bits_to_float(bits["a"][:, ks]), I.bf16_bits_to_float(bits["dqkv"][:, ns])
+    ref_dw = np.diagonal(L.linear_bwd_ref(a_cols, wf[np.ix_(ks, ns)], g_cols)["dw"])  # dw[ks[i], ns[i]]
+    idx = lambda r, c: (torch.from_numpy(r).cuda(), torch.from_numpy(c).cuda())
+    # the tolerances take the rms over the sample as the scale of the output
+    _check_bf16("qkv", G.to_f64(qkv[idx(ms, ns)]), ref_qkv)
+    _check_bf16("da", G.to_f64(da[idx(ms, ks)]), ref_da)
+    _check_f32("dw", G.to_f64(dw[idx(ks, ns)]), ref_dw)
+
+
 def test_layer_feeds_attention_in_place():
     """a[S*B, h] @ w[h, 3*H*D] lands in an [S, B, 3, H, D] buffer whose q, k, v views go straight
     into the strided attention forward; O is checked against the oracle on the layer's own
