@@ -19,13 +19,12 @@ import numpy as np
 
 PEAK_FLOP_PER_CLK_PER_CU = 4096          # dense bf16 MFMA, 4 SIMDs x 1024
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch at config 4 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
-# copy-kernel calibration (profiles/hbm_traffic_cfg4.md): fetched x2.00 + written x1.00.
+# HBM bytes per launch at config 4.  NOT measured by this program: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of
+# earlier runs of the same kernels at the same workload, scaled by the copy-kernel calibration
+# (profiles/hbm_traffic_cfg4.md: fetched x2.00 + written x1.00).  Reported under "traffic" with its source.
 TRAFFIC_CFG4_BYTES = {"fwd": (1.01e7 * 2 + 1.065e6) * 1024, "dkdv": (1.86e7 * 2 + 2.097e6) * 1024,
                       "dq": (1.18e7 * 2 + 1.049e6) * 1024}
-# Sustained rate of a pure v_mfma_f32_32x32x16_bf16 loop on the same chip (profiles/kernel_stats_cfg4.md):
-# the clock drops under the power limit when the operands are random.
-SUSTAINED_MFMA_TFLOPS = {"constant_operands": 2250.0, "random_operands": 1760.0}
+TRAFFIC_SOURCE = "profiles/hbm_traffic_cfg4.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not collected in this run)"
 
 
 def parse():
@@ -63,6 +62,32 @@ def parse():
     return ap.parse_args()
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def sustained_mfma(hx, torch, n_cu):
+    """The pure MFMA loop of the library, timed here and now: TFLOP/s with constant and with random operands."""
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    out = {}
+    for name, rnd in (("constant_operands", False), ("random_operands", True)):
+        hx.helix_mfma_probe(sink, 2 * n_cu, 2000, rnd)          # warm-up
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = hx.helix_mfma_probe(sink, 2 * n_cu, 100000, rnd)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return out
+
+
 def cpu_baseline(cfg, sample_tokens):
     """The oracle as it stands, timed on the host cores on a bounded sample."""
     from oracle import attention_ref as A
@@ -79,7 +104,7 @@ def cpu_baseline(cfg, sample_tokens):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = len(os.sched_getaffinity(0))
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle", "cpu": cpu_model(),
             "sample": f"oracle.attention_ref.head_backward (fp64 forward + gradients) on the first {S} tokens of head 0 "
                       f"of the workload, {dt:.1f} s"}
 
@@ -259,8 +284,8 @@ def linear_bench(args):
                                   f"w ~ N(0, 0.02^2), bf16", "M": M, "K": K, "N": N},
            "pct_of_bf16_mfma_peak": 100 * value / peak_tflops, "fwd_ms": ms_fwd, "bwd_ms": ms_bwd,
            "fwd_tflops": flops / ms_fwd / 1e9, "bwd_tflops": 2 * flops / ms_bwd / 1e9,
-           "roofline": {"bound": "mfma", "kernel": "gemm (forward)", "achieved": flops / ms_fwd / 1e9, "peak": 2500.0,
-                        "unit": "TFLOP/s", "frac": flops / ms_fwd / 1e9 / 2500.0,
+           "roofline": {"bound": "mfma", "kernel": "gemm (forward)", "achieved": flops / ms_fwd / 1e9, "peak": peak_tflops,
+                        "unit": "TFLOP/s", "frac": flops / ms_fwd / 1e9 / peak_tflops,
                         # profiles/hbm_traffic_qkv_linear.md: FETCH_SIZE x2 + WRITE_SIZE x1 of the forward product
                         "traffic": (1.21e6 * 2 + 3.933e5) * 1024 if (M, K, N) == (131072, 4096, 1536) else None,
                         "flops_per_launch": flops, "avg_launch_ms": ms_fwd}}
@@ -341,9 +366,12 @@ def main():
     ms_step = wall * 1e3 / args.steps
     value = 14 * unit / (wall / args.steps) / 1e12
     ms_bwd = ms["preprocess"] + ms["delta_head"] + ms["dkdv"] + ms["dq"]
-    # dominant kernel: the dK/dV pass (4 contractions = 8*D FLOPs per unmasked pair)
-    dom = max(("fwd", 4), ("dkdv", 8), ("dq", 6), key=lambda kv: ms[kv[0]])
-    dom_tflops = dom[1] * unit / (ms[dom[0]] * 1e-3) / 1e12
+    # dominant kernel: the dK/dV pass (4 contractions = 8*D FLOPs per unmasked pair, all of them part of the 10*D a
+    # recomputing backward needs)
+    flops_per_pair = {"fwd": 4, "dkdv": 8, "dq": 6}
+    executed = {n: f * unit / (ms[n] * 1e-3) / 1e12 for n, f in flops_per_pair.items()}
+    dom = max(flops_per_pair, key=lambda n: ms[n])
+    sustained = sustained_mfma(hx, torch, n_cu)
     pre_bytes = 2 * q.numel() * 2 + 3 * lse.numel() * 4   # reads O, dO, LSE; writes -delta and LSE*log2(e)
     out = {
         "metric": "causal attn fwd+bwd TFLOP/s @H=32,D=128,S=128k; % of bf16 MFMA peak",
@@ -360,15 +388,18 @@ def main():
         "bwd_tflops": 10 * unit / (ms_bwd * 1e-3) / 1e12,
         "fwd_bwd_tflops_table1_convention": 12 * unit / (wall / args.steps) / 1e12,
         "kernel_ms": ms,
-        "executed_tflops": {"fwd": 4 * unit / (ms["fwd"] * 1e-3) / 1e12, "dkdv": 8 * unit / (ms["dkdv"] * 1e-3) / 1e12,
-                            "dq": 6 * unit / (ms["dq"] * 1e-3) / 1e12},
-        "sustained_mfma_tflops_measured": SUSTAINED_MFMA_TFLOPS,
+        "executed_tflops": executed,
+        "executed_frac_of_peak": {n: x / peak_tflops for n, x in executed.items()},
+        "sustained_mfma_tflops_measured": sustained,
+        "pct_of_sustained_mfma_random": 100 * value / sustained["random_operands"],
         "preprocess_gbs": pre_bytes / (ms["preprocess"] * 1e-3) / 1e9,
         "preprocess_frac_of_hbm_peak": pre_bytes / (ms["preprocess"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"bound": "mfma", "kernel": dom[0], "achieved": dom_tflops, "peak": 2500.0, "unit": "TFLOP/s",
-                     "frac": dom_tflops / 2500.0,
-                     "traffic": TRAFFIC_CFG4_BYTES.get(dom[0]) if cfg.cfg_id == 4 else None,
-                     "flops_per_launch": dom[1] * unit, "avg_launch_ms": ms[dom[0]]},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": executed[dom], "peak": peak_tflops, "unit": "TFLOP/s",
+                     "frac": executed[dom] / peak_tflops,
+                     "traffic": TRAFFIC_CFG4_BYTES.get(dom) if cfg.cfg_id == 4 else None,
+                     "traffic_source": TRAFFIC_SOURCE if cfg.cfg_id == 4 else None,
+                     "flops_per_launch": flops_per_pair[dom] * unit, "avg_launch_ms": ms[dom],
+                     "whole_step_counted_frac": value / peak_tflops},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_tokens)

@@ -140,6 +140,15 @@ int helix_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d
  * factors of the MFMA roofline (CUs x 4096 bf16 FLOP/clk x clock).  Host pointers. */
 int helix_attn_device_info(int* compute_units, int* clock_khz);
 
+/* Measurement aid: enqueues a loop of independent 32x32x16 bf16 MFMA instructions and nothing
+ * else -- `workgroups` workgroups of 8 waves, `iters` x 16 instructions per wave -- and writes
+ * the number of FLOPs it performs to *flops (host).  Timed by the caller, it gives the rate the
+ * matrix pipes sustain on this chip, the practical ceiling of the attention kernels beside the
+ * nominal peak.  random_operands != 0: operand bits vary as on real data (the chip then lowers
+ * its clock under its power limit); 0: constant operands.  `sink` is a device float that the
+ * kernel never writes in practice; workgroups <= 2^20, iters <= 2^24. */
+int helix_mfma_probe(float* sink, int workgroups, int iters, int random_operands, long long* flops, void* stream);
+
 /* Human-readable name of a helix_status value (static storage, never NULL). */
 const char* helix_status_string(int status);
 

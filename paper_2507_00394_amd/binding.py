@@ -17,7 +17,7 @@ EXPORTS = ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_bwd_static", "helix_a
            "helix_attn_check_strides", "helix_qkv_linear_fwd", "helix_qkv_linear_bwd", "helix_qkv_linear_bwd_workspace_bytes",
            "helix_attn_bwd_workspace_bytes",
            "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head", "helix_attn_bwd_dkdv", "helix_attn_bwd_dq",
-           "helix_attn_device_info", "helix_status_string", "helix_attn_version")
+           "helix_attn_device_info", "helix_mfma_probe", "helix_status_string", "helix_attn_version")
 HELIX_OK = 0
 _lib = None
 
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.helix_attn_version.argtypes = []
         L.helix_attn_device_info.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.helix_attn_device_info.restype = i
+        L.helix_mfma_probe.argtypes = [fp, i, i, i, ctypes.POINTER(ctypes.c_longlong), vp]
+        L.helix_mfma_probe.restype = i
         for name in ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_fwd_strided", "helix_attn_bwd_strided",
                      "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head",
                      "helix_attn_bwd_dkdv",
@@ -118,6 +120,15 @@ def helix_attn_device_info():
     cu, khz = ctypes.c_int(0), ctypes.c_int(0)
     _raise(lib().helix_attn_device_info(ctypes.byref(cu), ctypes.byref(khz)), "helix_attn_device_info")
     return cu.value, khz.value
+
+
+def helix_mfma_probe(sink, workgroups, iters, random_operands, stream=None) -> int:
+    """Enqueues the pure MFMA loop; returns the FLOPs it performs.  `sink`: a CUDA float32 tensor with one element."""
+    _check_f32("sink", sink, (1,))
+    flops = ctypes.c_longlong(0)
+    _raise(lib().helix_mfma_probe(_ptr(sink), int(workgroups), int(iters), int(bool(random_operands)), ctypes.byref(flops),
+                                  _stream(stream)), "helix_mfma_probe")
+    return flops.value
 
 
 def helix_attn_bwd_workspace_bytes(B, H, S, D) -> int:

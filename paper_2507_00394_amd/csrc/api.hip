@@ -294,6 +294,14 @@ int helix_qkv_linear_bwd(const void* a, long long lda, const void* w, long long 
                                                   (hipStream_t)stream));
 }
 
+int helix_mfma_probe(float* sink, int workgroups, int iters, int random_operands, long long* flops, void* stream) {
+  if (!sink || !flops) return HELIX_ERR_NULL_POINTER;
+  if (!aligned(sink, 4)) return HELIX_ERR_MISALIGNED;
+  if (workgroups < 1 || iters < 1 || workgroups > (1 << 20) || iters > (1 << 24)) return HELIX_ERR_BAD_SHAPE;
+  *flops = helix::mfma_probe_flops(workgroups, iters);
+  return launched(helix::launch_mfma_probe(sink, workgroups, iters, random_operands != 0, (hipStream_t)stream));
+}
+
 int helix_attn_device_info(int* compute_units, int* clock_khz) {
   if (!compute_units || !clock_khz) return HELIX_ERR_NULL_POINTER;
   int dev = 0;

@@ -63,4 +63,8 @@ hipError_t launch_linear_bwd_input(const void* dout, long long ldd, const void* 
 hipError_t launch_linear_bwd_weight(const void* a, long long lda, const void* dout, long long ldd, float* dw, long long ldw,
                                     float* workspace, int M, int K, int N, hipStream_t stream);
 
+// Pure MFMA loop (mfma_probe.hip): `workgroups` x 8 waves x `iters` x 16 independent 32x32x16 bf16 MFMAs.
+long long mfma_probe_flops(int workgroups, int iters);
+hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, bool random_operands, hipStream_t stream);
+
 }  // namespace helix
