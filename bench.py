@@ -164,27 +164,6 @@ def share_bench(args):
         "roofline": None, "cpu_baseline": None}))
 
 
-def cu_masked_stream(n_cu, masked):
-    """A torch stream on which kernels may use all but `masked` compute units.  The withheld
-    units are mask bits 33*i mod n_cu, which spreads them over the XCDs whether consecutive
-    bits go round the XCDs or fill one XCD after the other."""
-    import ctypes
-
-    import torch
-
-    hip = ctypes.CDLL("libamdhip64.so")
-    words = (n_cu + 31) // 32
-    bits = [1] * n_cu
-    for i in range(masked):
-        bits[(33 * i) % n_cu] = 0
-    mask = (ctypes.c_uint32 * words)(*[sum(bits[32 * w + b] << b for b in range(32) if 32 * w + b < n_cu) for w in range(words)])
-    stream = ctypes.c_void_p()
-    err = hip.hipExtStreamCreateWithCUMask(ctypes.byref(stream), ctypes.c_uint32(words), mask)
-    if err != 0:
-        raise RuntimeError(f"hipExtStreamCreateWithCUMask failed with {err}")
-    return torch.cuda.ExternalStream(stream.value)
-
-
 def overlap_bench(args, step, flops_per_step):
     """Times `step` alone, then under the chosen disturbance; prints one JSON line."""
     import torch
@@ -228,6 +207,8 @@ def overlap_bench(args, step, flops_per_step):
         info.update({"copy_mib": args.copy_mib, "copies": copies, "copy_gbs_each_way": copies * n / dt / 1e9,
                      "paced_to_gbs": args.copy_gbs or None})
     else:
+        from paper_2507_00394_amd.streams import cu_masked_stream
+
         t, _ = timed(args.steps, stream=cu_masked_stream(n_cu, args.masked_cus))
         info.update({"masked_cus": args.masked_cus, "cus": n_cu,
                      "slowdown_if_proportional": n_cu / (n_cu - args.masked_cus)})
