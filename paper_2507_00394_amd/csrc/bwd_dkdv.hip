@@ -59,13 +59,6 @@ __device__ __forceinline__ f32x16 join4(const f32x4 (&x)[4]) {
   return r;
 }
 
-__device__ __forceinline__ uint32_t pack_bf16_pair(float a, float b) {
-  typedef float f32x2 __attribute__((ext_vector_type(2)));
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  const f32x2 x = {a, b};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
-}
-
 template <int D>
 struct Geometry {
   static constexpr int KS = D / 16, DB = D / 32;
@@ -228,7 +221,8 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
   if (t_hi < t_lo) t_hi = t_lo;
 
   const TileLoader<D, BM, 4> qload(lane, w, maps.q.row), gload(lane, w, maps.dO.row);
-  constexpr int NDMA = 2 * TileLoader<D, BM, 4>::N + 2;      // copy instructions per wave and tile
+  constexpr int kStatCopies = 2;                             // lse2 and -delta of the tile's rows, one instruction each
+  constexpr int NDMA = decltype(qload)::N + decltype(gload)::N + kStatCopies;   // copy instructions per wave and tile: what copy_tile() issues
   int t = 0, st = 0;                                          // tile and its stage (t % 4)
   auto copy_tile = [&](int tt, int stage) __attribute__((always_inline)) {
     const uint32_t sb = base + stage * G::STAGE;
@@ -237,8 +231,9 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
     gload.issue(gh, row0, S, sb + G::TILE);
     int r = row0 + lane;
     r = r < S ? r : S - 1;
-    dma_dword(lse_h, (uint32_t)r * 4, sb + G::STATS + w * 512);
-    dma_dword(delta_h, (uint32_t)r * 4, sb + G::STATS + w * 512 + 256);
+    const float* const stat[kStatCopies] = {lse_h, delta_h};
+#pragma unroll
+    for (int i = 0; i < kStatCopies; i++) dma_dword(stat[i], (uint32_t)r * 4, sb + G::STATS + w * 512 + 256 * i);
   };
   auto copy_ahead = [&]() __attribute__((always_inline)) {
     if (t + 3 < nt) copy_tile(t + 3, (st + 3) & 3);   // replaces tile t-1
@@ -314,15 +309,12 @@ bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, cons
     const uint32_t sbase = base + st * G::STAGE;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) pp.aq[ks] = sbase + lds_chunk_off<D>(n, 2 * ks + half);
-    {
-      const int i = lane & 15;
 #pragma unroll
-      for (int db = 0; db < DB; db++) {
-        const int col = 32 * db + ((lane >> 4) & 1) * 16 + (i & 3) * 4;
-        const int r0 = half * 4 + (i >> 2);
-        pp.at[db][0] = sbase + lds_chunk_off<D>(r0, col >> 3) + (col & 7) * 2;
-        pp.at[db][1] = sbase + lds_chunk_off<D>(r0 + 8, col >> 3) + (col & 7) * 2;
-      }
+    for (int db = 0; db < DB; db++) {
+      int o0, o1;
+      tr_pair_offsets<D>(lane, db, o0, o1);
+      pp.at[db][0] = sbase + o0;
+      pp.at[db][1] = sbase + o1;
     }
     pp.astat = sbase + G::STATS + w * 512 + half * 16;
     f32x16 spA, dpA, spB, dpB;

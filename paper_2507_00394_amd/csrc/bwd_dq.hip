@@ -31,13 +31,6 @@ namespace {
 
 constexpr int kRing = 4;   // A operands in flight
 
-__device__ __forceinline__ uint32_t pack_pair(float a, float b) {
-  typedef float f32x2 __attribute__((ext_vector_type(2)));
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  const f32x2 x = {a, b};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
-}
-
 // One pipelined half step.  B_HALF: h is the second half of its tile, so the block ahead
 // (h+1) lives in the next tile: the lane addresses move on by stage_step as soon as their
 // last read of the current tile is out.  On entry s_cur = S^T(h) with entries 0..7 already
@@ -102,7 +95,7 @@ __device__ __forceinline__ void dq_half_step(f32x16& s_cur, f32x16& s_next, bf16
       for (int e = (s - KS) * ED; e < (s - KS + 1) * ED; e += 2) {
         const float d0 = s_cur[e] * dp[e];
         const float d1 = s_cur[e + 1] * dp[e + 1];
-        sk[e / 2] = pack_pair(d0, d1);
+        sk[e / 2] = pack_bf16_pair(d0, d1);
       }
     } else {
 #pragma unroll
@@ -174,7 +167,7 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
   else { n_w = n_tiles; n_full = S / BN; }
 
   const TileLoader<D, BN, 8> kload(lane, w, maps.k.row), vload(lane, w, maps.v.row);
-  constexpr int NDMA = 2 * TileLoader<D, BN, 8>::N;
+  constexpr int NDMA = decltype(kload)::N + decltype(vload)::N;   // copy instructions per wave and tile: what copy_tile() issues
   int j = 0, st = 0;   // tile and its stage (j % 4)
   auto copy_tile = [&](int jj, int stage) __attribute__((always_inline)) {
     kload.issue(kh, jj * BN, S, base + stage * STAGE);
@@ -201,15 +194,12 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
   uint32_t ab[KS], at[DB][2];
 #pragma unroll
   for (int ks = 0; ks < KS; ks++) ab[ks] = base + lds_chunk_off<D>(n, 2 * ks + half);
-  {
-    const int i = lane & 15;
 #pragma unroll
-    for (int db = 0; db < DB; db++) {
-      const int col = 32 * db + ((lane >> 4) & 1) * 16 + (i & 3) * 4;
-      const int r0 = half * 4 + (i >> 2);
-      at[db][0] = base + lds_chunk_off<D>(r0, col >> 3) + (col & 7) * 2;
-      at[db][1] = base + lds_chunk_off<D>(r0 + 8, col >> 3) + (col & 7) * 2;
-    }
+  for (int db = 0; db < DB; db++) {
+    int o0, o1;
+    tr_pair_offsets<D>(lane, db, o0, o1);
+    at[db][0] = base + o0;
+    at[db][1] = base + o1;
   }
 
   // Prime: S^T of the first half tile (entries 0..7 exponentiated) and its first V operands.

@@ -37,16 +37,11 @@ struct FwdLaneAddr {
   int k[D / 16];       // K operand, contraction step ks, key row n of a tile (+32 rows by immediate)
   int v[D / 32][2];    // V^T operand of head-dim block db: first / second group of 4 key rows
   __device__ __forceinline__ FwdLaneAddr(int lane) {
-    const int half = lane >> 5, n = lane & 31, i = lane & 15;
+    const int half = lane >> 5, n = lane & 31;
 #pragma unroll
     for (int ks = 0; ks < D / 16; ks++) k[ks] = lds_chunk_off<D>(n, 2 * ks + half);
 #pragma unroll
-    for (int db = 0; db < D / 32; db++) {
-      const int col = 32 * db + ((lane >> 4) & 1) * 16 + (i & 3) * 4;
-      const int r0 = half * 4 + (i >> 2);
-      v[db][0] = lds_chunk_off<D>(r0, col >> 3) + (col & 7) * 2;
-      v[db][1] = lds_chunk_off<D>(r0 + 8, col >> 3) + (col & 7) * 2;
-    }
+    for (int db = 0; db < D / 32; db++) tr_pair_offsets<D>(lane, db, v[db][0], v[db][1]);
   }
 };
 
@@ -142,17 +137,12 @@ __device__ __forceinline__ float half_step(const f32x16& s_cur, f32x16& s_next,
   constexpr int RING = KS / 2;                              // operands in flight (== DB)
   constexpr int HALF = 32 * D * 2;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  typedef float f32x2 __attribute__((ext_vector_type(2)));
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   float ev[16];     // exp2 values, each alive until its pair is packed
   uint32_t pw[8];   // bf16 pairs of P
   auto element = [&](int x) {
     ev[x] = __builtin_amdgcn_exp2f(fmaf(s_cur[x], c, -st.mref_c));
     st.lsum[x & 1] += ev[x];
-    if (x & 1) {
-      const f32x2 pr = {ev[x - 1], ev[x]};
-      pw[x / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
-    }
+    if (x & 1) pw[x / 2] = pack_bf16_pair(ev[x - 1], ev[x]);
   };
 #pragma unroll
   for (int i = 0; i < KS; i++) {
@@ -241,6 +231,7 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   else { n_w = n_tiles; n_full = S / BN; }
 
   const TileLoader<D, BN, 8> kload(lane, w, maps.k.row), vload(lane, w, maps.v.row);
+  constexpr int NDMA = decltype(kload)::N + decltype(vload)::N;   // copy instructions per wave and tile: what copy_ahead() issues
   kload.issue(kh, 0, S, base);
   vload.issue(vh, 0, S, base + VREGION);
   if (n_tiles > 1) { kload.issue(kh, BN, S, base + TILE); vload.issue(vh, BN, S, base + VREGION + TILE); }
@@ -290,7 +281,7 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
   auto finish_tile = [&]() __attribute__((always_inline)) {
     // K(j+2) and V(j+2), issued one iteration ago, must have landed; this iteration's copies
     // (2 + 2 instructions per wave) may stay in flight.
-    if (j + 3 < n_tiles) wait_tile_loads_except<2 * TileLoader<D, BN, 8>::N>();
+    if (j + 3 < n_tiles) wait_tile_loads_except<NDMA>();
     else wait_tile_loads();
     __syncthreads();
     rk = (rk + 1) & 3;

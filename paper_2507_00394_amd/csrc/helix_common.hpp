@@ -118,7 +118,7 @@ struct TileLoader {
   static constexpr int CH = D / 8;                        // 16-byte chunks per row
   static constexpr int ROWS_PER_KB = 64 / CH;             // rows covered by one wave instruction
   static constexpr int KB = ROWS / ROWS_PER_KB;           // 1 KB pieces in the tile
-  static constexpr int N = (KB + NWAVES - 1) / NWAVES;    // pieces per wave
+  static constexpr int N = (KB + NWAVES - 1) / NWAVES;    // pieces per wave = copy instructions one issue() costs a wave
   static_assert(KB % NWAVES == 0, "every wave copies the same number of pieces");
   int wave, lane_row;  // lane_row: this lane's row inside a piece
   uint32_t row_bytes;  // distance between consecutive rows of the tensor in global memory
@@ -190,6 +190,26 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(uint32_t addr0, uint32_t addr1, in
   const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HELIX_LDS(s16x4, reinterpret_cast<lds_ptr>((uintptr_t)addr1) + imm));
   const s16x8 ab = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, ab);
+}
+
+// Byte offsets, inside a swizzled [rows][D] tile, of the two transposing reads that give lane
+// `lane` its MFMA operand for columns 32*db .. 32*db+31: rows 4*(lane/32) + 0..3 and, 8 rows
+// further, the second group (the slot order of a bf16 pack of accumulator registers 8t..8t+7).
+template <int D>
+__device__ __forceinline__ void tr_pair_offsets(int lane, int db, int& off0, int& off1) {
+  const int i = lane & 15;
+  const int col = 32 * db + ((lane >> 4) & 1) * 16 + (i & 3) * 4;
+  const int r0 = (lane >> 5) * 4 + (i >> 2);
+  off0 = lds_chunk_off<D>(r0, col >> 3) + (col & 7) * 2;
+  off1 = lds_chunk_off<D>(r0 + 8, col >> 3) + (col & 7) * 2;
+}
+
+// Two fp32 values rounded to nearest-even bf16 and packed into one register (low half first).
+__device__ __forceinline__ uint32_t pack_bf16_pair(float a, float b) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 x = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
 
 // Forces a value loaded from global memory to be complete at this point of the program.

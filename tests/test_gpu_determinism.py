@@ -27,3 +27,23 @@ def test_repeated_runs_are_bit_identical(BH, S, D, causal):
             continue
         for n in cur:
             assert torch.equal(cur[n], first[n]), f"{n} differs from the first run in repetition {rep}"
+
+
+def test_repeated_runs_at_the_7b_32k_size():
+    """Three runs of config 3 (B=1, H=32, S=32768, D=128): every wave goes round the four-stage tile
+    pipelines some hundreds of times, the length at which a mis-counted copy wait would show."""
+    from tests import gpu_util as G
+
+    cfg = I.CONFIGS[3]
+    bits = I.all_inputs_bits(cfg, threads=16)
+    first = None
+    for rep in range(3):
+        out = G.run_fwd_bwd(bits, cfg.scale, True)
+        cur = {n: (out[n].view(torch.int16) if out[n].dtype == torch.bfloat16 else out[n]).clone()
+               for n in ("o", "lse", "dq", "dk", "dv")}
+        del out
+        if first is None:
+            first = cur
+            continue
+        for n in cur:
+            assert torch.equal(cur[n], first[n]), f"{n} differs from the first run in repetition {rep}"
