@@ -8,7 +8,7 @@ import sys
 
 CSRC = pathlib.Path(__file__).resolve().parent / "csrc"
 LIB = CSRC / "libhelix_attn.so"
-SOURCES = ["api.hip", "fwd.hip", "bwd.hip", "bwd_dkdv.hip", "bwd_dq.hip", "linear.hip", "mfma_probe.hip"]
+SOURCES = ["api.hip", "fwd.hip", "bwd.hip", "bwd_dkdv.hip", "bwd_dkdv_pair.hip", "bwd_dq.hip", "linear.hip", "mfma_probe.hip"]
 # Packed fp32 VALU ops are switched off for the device pass; the host pass does not know
 # the feature and says so in a harmless warning.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -383,6 +383,9 @@ static hipError_t launch_dkdv_t(const void* q, const void* k, const void* v, con
 hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* dO,
                            const float* lse2, const float* neg_delta, void* dk, void* dv, const BwdMaps& maps,
                            int B, int H, int S, int D, float scale, bool causal, hipStream_t stream) {
+#ifndef HELIX_DKDV_ONE_WAVE
+  if (D == 128) return launch_bwd_dkdv_pair(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, causal, stream);
+#endif
   if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, stream)
                               : launch_dkdv_t<128, false>(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, stream);
   return causal ? launch_dkdv_t<64, true>(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, stream)

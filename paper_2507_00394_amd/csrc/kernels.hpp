@@ -45,6 +45,10 @@ hipError_t launch_bwd_delta_head(const void* q, const void* k, const void* v, co
 hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* dO,
                            const float* lse2, const float* neg_delta, void* dk, void* dv, const BwdMaps& maps,
                            int B, int H, int S, int D, float scale, bool causal, hipStream_t stream);
+// Head dimension 128 with two waves per SIMD (one wave of a pair for S, P and dV, the other for dP, dS and dK).
+hipError_t launch_bwd_dkdv_pair(const void* q, const void* k, const void* v, const void* dO, const float* lse2,
+                                const float* neg_delta, void* dk, void* dv, const BwdMaps& maps, int B, int H, int S,
+                                float scale, bool causal, hipStream_t stream);
 hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void* dO,
                          const float* lse2, const float* neg_delta, void* dq, const BwdMaps& maps,
                          int B, int H, int S, int D, float scale, bool causal, hipStream_t stream);
