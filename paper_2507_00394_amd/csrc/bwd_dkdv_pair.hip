@@ -158,12 +158,13 @@ __device__ __forceinline__ void step_a(f32x16& s_cur, f32x16& s_next, bf16x8 (&r
         ring[s % 4] = lds_tr_pair(ln.at[i % DB][0], ln.at[i % DB][1], stage_imm(K) + 16 * (i / DB) * G::D * 2);
       } else ring[s % 4] = lds_b128(ln.aq[u - 2 * KS], stage_imm(KP));
     }
-    // ---- lse2, four rows at a time, two slots ahead of the four slots that use them: groups 2, 3 of
-    // block i in slots 0..3, 4..7, groups 0, 1 of block i+1 in slots 8..11, 12..15
-    if constexpr (s == 2) l2[1] = lds_f32x4(ln.astat, K * G::STAT_STAGE + 8 * 3 * 4);
-    if constexpr (s == 6) l2[0] = lds_f32x4(ln.astat, KN * G::STAT_STAGE);
-    if constexpr (s == 10) l2[1] = lds_f32x4(ln.astat, KN * G::STAT_STAGE + 8 * 1 * 4);
-    if constexpr (s == 14) l2[0] = lds_f32x4(ln.astat, KN * G::STAT_STAGE + 8 * 2 * 4);
+    // ---- lse2, four rows at a time, four slots ahead of the four slots that use them (as soon as the
+    // register quad is free): groups 2, 3 of block i are used in slots 0..3, 4..7, groups 0, 1 of
+    // block i+1 in slots 8..11, 12..15
+    if constexpr (s == 0) l2[1] = lds_f32x4(ln.astat, K * G::STAT_STAGE + 8 * 3 * 4);
+    if constexpr (s == 4) l2[0] = lds_f32x4(ln.astat, KN * G::STAT_STAGE);
+    if constexpr (s == 8) l2[1] = lds_f32x4(ln.astat, KN * G::STAT_STAGE + 8 * 1 * 4);
+    if constexpr (s == 12) l2[0] = lds_f32x4(ln.astat, KN * G::STAT_STAGE + 8 * 2 * 4);
     // ---- vector work
     if constexpr (s < KS) {
       // second half of P(i); packs of the first half
@@ -230,9 +231,10 @@ __device__ __forceinline__ void step_b(f32x16& dp_cur, f32x16& dp_next, bf16x8 (
     if constexpr (s == 2) copy_whole_block<wrap(K + G::AHEAD)>(cp);
     // ---- -delta of block i+1 (the registers are free once the dP product has started)
     if constexpr (s >= 12) nd[s - 12] = lds_f32x4(ln.astat, KN * G::STAT_STAGE + 8 * (s - 12) * 4);
-    // ---- vector work: dS(j) = P(j) o dP(j), two elements per slot in slots 2..5 (first half) and 8..11 (second half)
-    if constexpr (!SKIP && ((s >= 2 && s < 6) || (s >= 8 && s < 12))) {
-      constexpr int e0 = s < 6 ? 2 * (s - 2) : 8 + 2 * (s - 8);
+    // ---- vector work: dS(j) = P(j) o dP(j), two elements per slot in slots 4..7 (first half, P was
+    // requested in slot 0) and 8..11 (second half)
+    if constexpr (!SKIP && s >= 4 && s < 12) {
+      constexpr int e0 = 2 * (s - 4);
       const float d0 = pf[e0 / 4][e0 % 4] * dp_cur[e0];
       const float d1 = pf[(e0 + 1) / 4][(e0 + 1) % 4] * dp_cur[e0 + 1];
       sk[e0 / 2] = pack_bf16_pair(d0, d1);
