@@ -35,8 +35,8 @@ constexpr int kRing = 4;   // A operands in flight
 // (h+1) lives in the next tile: the lane addresses move on by stage_step as soon as their
 // last read of the current tile is out.  On entry s_cur = S^T(h) with entries 0..7 already
 // exponentiated and ring = first four V(h) operands; on exit the same holds for s_next.
-template <int D, bool B_HALF>
-__device__ __forceinline__ void dq_half_step(f32x16& s_cur, f32x16& s_next, bf16x8 (&ring)[kRing],
+template <int D, bool B_HALF, typename Copy>
+__device__ __forceinline__ void dq_half_step(const Copy& copy_tile, f32x16& s_cur, f32x16& s_next, bf16x8 (&ring)[kRing],
                                              const bf16x8 (&qf)[D / 16], const bf16x8 (&gf)[D / 16],
                                              f32x16 (&dqacc)[D / 32], uint32_t (&ab)[D / 16], uint32_t (&at)[D / 32][2],
                                              int stage_step, float c, float lse2, const f32x16& nd) {
@@ -64,6 +64,7 @@ __device__ __forceinline__ void dq_half_step(f32x16& s_cur, f32x16& s_next, bf16
       const u32x4 b = {sk[4 * (i / DB)], sk[4 * (i / DB) + 1], sk[4 * (i / DB) + 2], sk[4 * (i / DB) + 3]};
       dqacc[i % DB] = mfma32(ring[s % R], __builtin_bit_cast(bf16x8, b), dqacc[i % DB]);
     }
+    if (s == 1) copy_tile();   // tile copies are issued under the first MFMAs, not in front of them
     // ---- lane addresses move to the next tile
     if (B_HALF && s == KS - R) {
 #pragma unroll
@@ -216,11 +217,24 @@ bwd_dq_pipe_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, c
     for (int i = 0; i < kRing; i++) ring[i] = lds_b128(ab[i], TILE);
   }
 
+  const auto no_copy = []() {};
   for (; j < n_w - 1; j++) {
-    copy_ahead();
+    // A complete tile j+3 is copied by a handful of instructions issued inside the half step; a
+    // ragged one (the last of the sequence) takes the general path in front of it.
+    const bool whole = j + 3 < n_tiles && (j + 4) * BN <= S;
+    if (!whole) copy_ahead();
+    const __bf16* kt = kload.tile_ptr(kh, (j + 3) * BN);
+    const __bf16* vt = vload.tile_ptr(vh, (j + 3) * BN);
+    const uint32_t dst = base + ((st + 3) & 3) * STAGE;
+    const auto copy_whole = [&]() __attribute__((always_inline)) {
+      if (whole) {
+        kload.issue_whole(kt, dst);
+        vload.issue_whole(vt, dst + TILE);
+      }
+    };
     const int stage_step = (st == 3) ? -3 * STAGE : STAGE;
-    dq_half_step<D, false>(sa, sb, ring, qf, gf, dqacc, ab, at, stage_step, c, lse2, nd);
-    dq_half_step<D, true>(sb, sa, ring, qf, gf, dqacc, ab, at, stage_step, c, lse2, nd);
+    dq_half_step<D, false>(copy_whole, sa, sb, ring, qf, gf, dqacc, ab, at, stage_step, c, lse2, nd);
+    dq_half_step<D, true>(no_copy, sb, sa, ring, qf, gf, dqacc, ab, at, stage_step, c, lse2, nd);
     finish_tile();
   }
 

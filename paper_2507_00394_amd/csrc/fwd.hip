@@ -127,8 +127,8 @@ __device__ __forceinline__ void pv_block(const uint32_t (&vaddr)[D / 32][2], int
 // When LAST_OF_TILE the next step works on the next V tile: vaddr moves on by v_step once this
 // tile's reads are issued.
 constexpr int kExpInScoreSlots = 10;
-template <int D, int K_CUR, int K_NEXT, int V_IMM, bool LAST_OF_TILE>
-__device__ __forceinline__ float half_step(const f32x16& s_cur, f32x16& s_next,
+template <int D, int K_CUR, int K_NEXT, int V_IMM, bool LAST_OF_TILE, typename Copy>
+__device__ __forceinline__ float half_step(const Copy& copy_tile, const f32x16& s_cur, f32x16& s_next,
                                            bf16x8 (&kop)[D / 32], bf16x8 (&vop)[D / 32], const bf16x8 (&qf)[D / 16],
                                            const uint32_t (&klo)[D / 32], const uint32_t (&khi)[D / 32],
                                            uint32_t (&vaddr)[D / 32][2], int v_step,
@@ -148,6 +148,7 @@ __device__ __forceinline__ float half_step(const f32x16& s_cur, f32x16& s_next,
   for (int i = 0; i < KS; i++) {
     s_next = mfma32(kop[i % RING], qf[i], i == 0 ? zero : s_next);
     if (i < RING) kop[i] = lds_b128(khi[i], K_CUR);
+    if (i == 1) copy_tile();   // tile copies are issued under the first MFMAs, not in front of them
 #pragma unroll
     for (int x = 0; x < kExpInScoreSlots; x++)
       if (x * KS / kExpInScoreSlots == i) element(x);
@@ -287,19 +288,32 @@ fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __b
     rk = (rk + 1) & 3;
   };
 
+  const auto no_copy = []() {};
   for (; j < n_w - 1; j++) {
-    copy_ahead();
     const int khi_step = (rk == 3) ? -3 * TILE : TILE;   // K buffer of tile j   -> j+1
     const int klo_step = (rk == 2) ? -3 * TILE : TILE;   // K buffer of tile j+1 -> j+2
     const int v_step = khi_step;                         // V buffer of tile j   -> j+1
     // half a: score S_b(j) | P_a(j) | O += V_a(j) P_a(j) | read K_b(j) 4..7, K_a(j+1) 0..3
-    const float mb = half_step<D, HALF, 0, 0, false>(sa, sb, kop, vop, qf, klo, khi, vaddr, v_step, oacc, c, st);
+    // A complete tile j+3 is copied by a handful of instructions issued inside the half step; a
+    // ragged one (the last of the sequence) takes the general path in front of it.
+    const bool whole = j + 3 < n_tiles && (j + 4) * BN <= S;
+    if (!whole) copy_ahead();
+    const __bf16* kt = kload.tile_ptr(kh, (j + 3) * BN);
+    const __bf16* vt = vload.tile_ptr(vh, (j + 3) * BN);
+    const uint32_t dst = base + ((rk + 3) & 3) * TILE;
+    const auto copy_whole = [&]() __attribute__((always_inline)) {
+      if (whole) {
+        kload.issue_whole(kt, dst);
+        vload.issue_whole(vt, dst + VREGION);
+      }
+    };
+    const float mb = half_step<D, HALF, 0, 0, false>(copy_whole, sa, sb, kop, vop, qf, klo, khi, vaddr, v_step, oacc, c, st);
     check_reference<DB>(mb, c, st, oacc);
 #pragma unroll
     for (int i = 0; i < DB; i++) khi[i] += khi_step;
     // half b: score S_a(j+1) | P_b(j) | O += V_b(j) P_b(j) | read K_a(j+1) 4..7, K_b(j+1) 0..3;
     // vaddr moves to V(j+1)
-    const float ma = half_step<D, 0, HALF, HALF, true>(sb, sa, kop, vop, qf, klo, khi, vaddr, v_step, oacc, c, st);
+    const float ma = half_step<D, 0, HALF, HALF, true>(no_copy, sb, sa, kop, vop, qf, klo, khi, vaddr, v_step, oacc, c, st);
     if (j + 1 < n_w - 1) check_reference<DB>(ma, c, st, oacc);   // the plain path masks first
 #pragma unroll
     for (int i = 0; i < DB; i++) klo[i] += klo_step;

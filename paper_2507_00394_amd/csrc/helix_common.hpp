@@ -133,18 +133,25 @@ struct TileLoader {
       off[i] = r * row_bytes + (((lane % CH) ^ swizzle<D>(r)) << 4);
     }
   }
+  // Address of the tile's first row (wave-uniform, in scalar registers).
+  __device__ __forceinline__ const __bf16* tile_ptr(const __bf16* head_base, int row0) const {
+    return uniform_ptr(reinterpret_cast<const __bf16*>(reinterpret_cast<const char*>(head_base) + (size_t)row0 * row_bytes));
+  }
+  // Copy of a tile all of whose ROWS rows exist: N instructions, no branch.
+  __device__ __forceinline__ void issue_whole(const __bf16* tile_base, uint32_t lds_tile_addr) const {
+#pragma unroll
+    for (int i = 0; i < N; i++) {
+      const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile_addr + (wave + NWAVES * i) * 1024);
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                   :: "v"(off[i]), "s"(tile_base), "s"(dst) : "memory");
+    }
+  }
   // lds_tile_addr: 32-bit LDS address of the destination tile (wave-uniform).
   __device__ __forceinline__ void issue(const __bf16* head_base, int row0, int nrows, uint32_t lds_tile_addr) const {
-    const __bf16* tile_base = uniform_ptr(reinterpret_cast<const __bf16*>(
-        reinterpret_cast<const char*>(head_base) + (size_t)row0 * row_bytes));
+    const __bf16* tile_base = tile_ptr(head_base, row0);
     const int last = __builtin_amdgcn_readfirstlane(nrows - 1 - row0);   // last valid tile row (>= ROWS-1 unless ragged)
     if (last >= ROWS - 1) {
-#pragma unroll
-      for (int i = 0; i < N; i++) {
-        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile_addr + (wave + NWAVES * i) * 1024);
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                     :: "v"(off[i]), "s"(tile_base), "s"(dst) : "memory");
-      }
+      issue_whole(tile_base, lds_tile_addr);
     } else {   // last tile of a ragged sequence: clamp the row
 #pragma unroll
       for (int i = 0; i < N; i++) {
