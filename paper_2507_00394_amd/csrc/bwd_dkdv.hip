@@ -1,4 +1,6 @@
-// dK / dV pass of the attention backward for gfx950 (Table 1, Attention column, "Backward B").
+// dK / dV pass of the attention backward for gfx950 (Table 1, Attention column, "Backward B"),
+// one wave per SIMD.  The launcher at the end uses it for head dimension 64; head dimension 128
+// goes to the two-waves-per-SIMD kernel in bwd_dkdv_pair.hip (same arithmetic).
 //
 // Work split: a workgroup of 4 waves owns 128 keys of one (batch, head) slice, 32 keys per
 // wave, and sweeps the 64-row query tiles that see them.  Per 32-row query block b a wave
@@ -383,11 +385,8 @@ static hipError_t launch_dkdv_t(const void* q, const void* k, const void* v, con
 hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* dO,
                            const float* lse2, const float* neg_delta, void* dk, void* dv, const BwdMaps& maps,
                            int B, int H, int S, int D, float scale, bool causal, hipStream_t stream) {
-#ifndef HELIX_DKDV_ONE_WAVE
+  // Head dimension 128 has its own kernel with two waves per SIMD; this one serves head dimension 64.
   if (D == 128) return launch_bwd_dkdv_pair(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, causal, stream);
-#endif
-  if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, stream)
-                              : launch_dkdv_t<128, false>(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, stream);
   return causal ? launch_dkdv_t<64, true>(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, stream)
                 : launch_dkdv_t<64, false>(q, k, v, dO, lse2, neg_delta, dk, dv, maps, B, H, S, scale, stream);
 }
