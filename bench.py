@@ -22,8 +22,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch at config 4.  NOT measured by this program: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of
 # earlier runs of the same kernels at the same workload, scaled by the copy-kernel calibration
 # (profiles/hbm_traffic_cfg4.md: fetched x2.00 + written x1.00).  Reported under "traffic" with its source.
-TRAFFIC_CFG4_BYTES = {"fwd": (1.01e7 * 2 + 1.065e6) * 1024, "dkdv": (1.86e7 * 2 + 2.097e6) * 1024,
-                      "dq": (1.18e7 * 2 + 1.049e6) * 1024}
+TRAFFIC_CFG4_BYTES = {"fwd": (9.704e6 * 2 + 1.065e6) * 1024, "dkdv": (1.860e7 * 2 + 2.097e6) * 1024,
+                      "dq": (1.238e7 * 2 + 1.049e6) * 1024}
 TRAFFIC_SOURCE = "profiles/hbm_traffic_cfg4.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not collected in this run)"
 
 
