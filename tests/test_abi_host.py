@@ -82,6 +82,16 @@ def test_validation_precedes_any_device_work(L):
     assert L.helix_attn_bwd_dq(p, p, p, p, p, p, 1, 1, 8, 128, -0.1, 1, None) == 5
 
 
+def test_mfma_probe_validation(L):
+    p = ctypes.c_void_p(0x10000)
+    flops = ctypes.c_longlong(-1)
+    call = lambda sink=p, wg=4, it=10, out=ctypes.byref(flops): L.helix_mfma_probe(sink, wg, it, 1, out, None)
+    assert call(sink=None) == 1 and call(out=None) == 1
+    assert call(sink=ctypes.c_void_p(0x10002)) == 4
+    assert call(wg=0) == 2 and call(it=0) == 2 and call(wg=(1 << 20) + 1) == 2 and call(it=(1 << 24) + 1) == 2
+    assert flops.value == -1          # nothing was written by a refused call
+
+
 def test_stride_validation(L):
     """Strided entry points: the stride rules of the header, checked on the host."""
     p = ctypes.c_void_p(0x10000)
