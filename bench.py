@@ -85,6 +85,17 @@ def sustained_mfma(hx, torch, n_cu):
         e1.record()
         torch.cuda.synchronize()
         out[name] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    # the same loop with the instruction mix of the kernels: 1 LDS operand read per MFMA + 2 fma + 0.5 exp2
+    # (backward passes) or + 3 fma + 1 exp2 (forward); one workgroup of 8 waves per compute unit
+    for name, fwd_mix in (("random_operands_backward_mix", False), ("random_operands_forward_mix", True)):
+        hx.helix_mfma_mix_probe(sink, n_cu, 4000, fwd_mix)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = hx.helix_mfma_mix_probe(sink, n_cu, 150000, fwd_mix)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
     return out
 
 
@@ -373,6 +384,11 @@ def main():
         "executed_frac_of_peak": {n: x / peak_tflops for n, x in executed.items()},
         "sustained_mfma_tflops_measured": sustained,
         "pct_of_sustained_mfma_random": 100 * value / sustained["random_operands"],
+        # executed rate of each kernel over the rate of the MFMA loop that carries the same instruction mix
+        # (one LDS operand read per MFMA + the kernel's vector work), measured in this run
+        "executed_frac_of_mix_probe": {"fwd": executed["fwd"] / sustained["random_operands_forward_mix"],
+                                       "dkdv": executed["dkdv"] / sustained["random_operands_backward_mix"],
+                                       "dq": executed["dq"] / sustained["random_operands_backward_mix"]},
         "preprocess_gbs": pre_bytes / (ms["preprocess"] * 1e-3) / 1e9,
         "preprocess_frac_of_hbm_peak": pre_bytes / (ms["preprocess"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": executed[dom], "peak": peak_tflops, "unit": "TFLOP/s",

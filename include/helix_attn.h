@@ -149,6 +149,14 @@ int helix_attn_device_info(int* compute_units, int* clock_khz);
  * kernel never writes in practice; workgroups <= 2^20, iters <= 2^24. */
 int helix_mfma_probe(float* sink, int workgroups, int iters, int random_operands, long long* flops, void* stream);
 
+/* Measurement aid: the loop of helix_mfma_probe (random operands) in the company an MFMA has in
+ * the attention kernels -- per MFMA one 1 KB operand read from LDS and, forward_mix == 0, two
+ * fused multiply-adds and half an exp2 (the mix of the two backward passes) or, forward_mix != 0,
+ * three and one (the forward's).  What it sustains is the rate a kernel with that instruction mix
+ * can reach with no barrier, tile copy or dependency in its way.  Same arguments, limits and FLOP
+ * count as helix_mfma_probe; uses 64 KB of LDS per workgroup. */
+int helix_mfma_mix_probe(float* sink, int workgroups, int iters, int forward_mix, long long* flops, void* stream);
+
 /* Human-readable name of a helix_status value (static storage, never NULL). */
 const char* helix_status_string(int status);
 

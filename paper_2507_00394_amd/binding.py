@@ -17,7 +17,7 @@ EXPORTS = ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_bwd_static", "helix_a
            "helix_attn_check_strides", "helix_qkv_linear_fwd", "helix_qkv_linear_bwd", "helix_qkv_linear_bwd_workspace_bytes",
            "helix_attn_bwd_workspace_bytes",
            "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head", "helix_attn_bwd_dkdv", "helix_attn_bwd_dq",
-           "helix_attn_device_info", "helix_mfma_probe", "helix_status_string", "helix_attn_version")
+           "helix_attn_device_info", "helix_mfma_probe", "helix_mfma_mix_probe", "helix_status_string", "helix_attn_version")
 HELIX_OK = 0
 _lib = None
 
@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.helix_attn_device_info.restype = i
         L.helix_mfma_probe.argtypes = [fp, i, i, i, ctypes.POINTER(ctypes.c_longlong), vp]
         L.helix_mfma_probe.restype = i
+        L.helix_mfma_mix_probe.argtypes = [fp, i, i, i, ctypes.POINTER(ctypes.c_longlong), vp]
+        L.helix_mfma_mix_probe.restype = i
         for name in ("helix_attn_fwd", "helix_attn_bwd", "helix_attn_fwd_strided", "helix_attn_bwd_strided",
                      "helix_attn_bwd_preprocess", "helix_attn_bwd_delta_head",
                      "helix_attn_bwd_dkdv",
@@ -128,6 +130,15 @@ def helix_mfma_probe(sink, workgroups, iters, random_operands, stream=None) -> i
     flops = ctypes.c_longlong(0)
     _raise(lib().helix_mfma_probe(_ptr(sink), int(workgroups), int(iters), int(bool(random_operands)), ctypes.byref(flops),
                                   _stream(stream)), "helix_mfma_probe")
+    return flops.value
+
+
+def helix_mfma_mix_probe(sink, workgroups, iters, forward_mix, stream=None) -> int:
+    """Enqueues the MFMA loop with LDS reads and vector work beside it; returns the FLOPs it performs."""
+    _check_f32("sink", sink, (1,))
+    flops = ctypes.c_longlong(0)
+    _raise(lib().helix_mfma_mix_probe(_ptr(sink), int(workgroups), int(iters), int(bool(forward_mix)), ctypes.byref(flops),
+                                      _stream(stream)), "helix_mfma_mix_probe")
     return flops.value
 
 

@@ -18,7 +18,7 @@ namespace {
 constexpr size_t kScratchBytes = HELIX_STATIC_SCRATCH_BYTES;
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
-constexpr int kVersion = 200;  // 0.2.0
+constexpr int kVersion = 300;  // 0.3.0: backward stages share one statistics workspace; probes; allocation-free backward
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -300,6 +300,14 @@ int helix_mfma_probe(float* sink, int workgroups, int iters, int random_operands
   if (workgroups < 1 || iters < 1 || workgroups > (1 << 20) || iters > (1 << 24)) return HELIX_ERR_BAD_SHAPE;
   *flops = helix::mfma_probe_flops(workgroups, iters);
   return launched(helix::launch_mfma_probe(sink, workgroups, iters, random_operands != 0, (hipStream_t)stream));
+}
+
+int helix_mfma_mix_probe(float* sink, int workgroups, int iters, int forward_mix, long long* flops, void* stream) {
+  if (!sink || !flops) return HELIX_ERR_NULL_POINTER;
+  if (!aligned(sink, 4)) return HELIX_ERR_MISALIGNED;
+  if (workgroups < 1 || iters < 1 || workgroups > (1 << 20) || iters > (1 << 24)) return HELIX_ERR_BAD_SHAPE;
+  *flops = helix::mfma_probe_flops(workgroups, iters);
+  return launched(helix::launch_mfma_mix_probe(sink, workgroups, iters, forward_mix != 0, (hipStream_t)stream));
 }
 
 int helix_attn_device_info(int* compute_units, int* clock_khz) {

@@ -70,5 +70,8 @@ hipError_t launch_linear_bwd_weight(const void* a, long long lda, const void* do
 // Pure MFMA loop (mfma_probe.hip): `workgroups` x 8 waves x `iters` x 16 independent 32x32x16 bf16 MFMAs.
 long long mfma_probe_flops(int workgroups, int iters);
 hipError_t launch_mfma_probe(float* sink, int workgroups, int iters, bool random_operands, hipStream_t stream);
+// The same loop with one LDS operand read and some vector work per MFMA: 2 fma + 0.5 exp2 (the backward passes'
+// mix) or, forward_mix, 3 fma + 1 exp2.  One workgroup per compute unit (64 KB of LDS).  Same FLOP count.
+hipError_t launch_mfma_mix_probe(float* sink, int workgroups, int iters, bool forward_mix, hipStream_t stream);
 
 }  // namespace helix

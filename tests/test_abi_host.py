@@ -90,6 +90,9 @@ def test_mfma_probe_validation(L):
     assert call(sink=ctypes.c_void_p(0x10002)) == 4
     assert call(wg=0) == 2 and call(it=0) == 2 and call(wg=(1 << 20) + 1) == 2 and call(it=(1 << 24) + 1) == 2
     assert flops.value == -1          # nothing was written by a refused call
+    mix = lambda sink=p, wg=4, it=10, out=ctypes.byref(flops): L.helix_mfma_mix_probe(sink, wg, it, 0, out, None)
+    assert mix(sink=None) == 1 and mix(out=None) == 1 and mix(sink=ctypes.c_void_p(0x10002)) == 4
+    assert mix(wg=0) == 2 and mix(it=0) == 2 and mix(wg=(1 << 20) + 1) == 2 and flops.value == -1
 
 
 def test_stride_validation(L):

@@ -30,6 +30,23 @@ def test_flop_count_rate_and_sink():
     assert float(sink.item()) == 7.0
     assert 0.4 * peak < rate[True] <= rate[False] * 1.02 and rate[False] < 1.01 * peak
 
+    # the loop with one LDS operand read and vector work per MFMA: same FLOP count, lower rate, the
+    # forward's mix (more vector work) below the backward's
+    mix = {}
+    for fwd_mix in (False, True):
+        hx.helix_mfma_mix_probe(sink, cus, 500, fwd_mix)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = hx.helix_mfma_mix_probe(sink, cus, iters, fwd_mix)
+        e1.record()
+        torch.cuda.synchronize()
+        assert flops == cus * 8 * iters * 16 * 2 * 32 * 32 * 16
+        mix[fwd_mix] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    print(f"with the kernels' instruction mix: backward-like {mix[False]:.0f}, forward-like {mix[True]:.0f} TFLOP/s", flush=True)
+    assert float(sink.item()) == 7.0
+    assert 0.3 * peak < mix[True] < mix[False] * 1.02 and mix[False] < rate[True] * 1.02
+
     s2 = torch.cuda.Stream()
     with torch.cuda.stream(s2):
         hx.helix_mfma_probe(sink, 8, 100, True, stream=s2)
