@@ -3,9 +3,10 @@
 // activations the paper calls "saved by flash attention" (Section 4.4) -- in three kernels:
 //
 //   preprocess : delta_i = sum_d dO_id * O_id                         (streams 2 tensors, HBM bound)
-//   dkdv       : (bwd_dkdv.hip) a workgroup owns 128 keys and sweeps the query tiles that see
-//                them: S = Q K^T, P = exp(scale*S - LSE), dV^T += dO^T P, dP = dO V^T,
-//                dS = P o (dP - delta), dK^T += Q^T dS
+//   dkdv       : (bwd_dkdv_pair.hip for head dimension 128, bwd_dkdv.hip for 64) a workgroup owns
+//                128 keys and sweeps the query blocks that see them: S = Q K^T,
+//                P = exp(scale*S - LSE), dV^T += dO^T P, dP = dO V^T, dS = P o (dP - delta),
+//                dK^T += Q^T dS
 //   dq         : (bwd_dq.hip) a workgroup owns 256 queries and sweeps the visible key tiles:
 //                S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T
 //   delta_head : the unpipelined variant of the dQ sweep kept in this file; it only produces
