@@ -19,8 +19,8 @@
 // small rings for lse2 / -delta.  The block loop is unrolled seven times, so the stage of
 // every LDS access is a compile-time immediate added to one of two anchor registers (the
 // offset field of an LDS instruction reaches 64 KB): the loop contains no address arithmetic
-// at all.  Blocks cut by the causal diagonal, the blocks up to the first multiple of seven
-// and whatever remains at the end run through a plain path (A, barrier, B, barrier).
+// at all.  Blocks cut by the causal diagonal and whatever remains at the end run through a
+// plain path (A, barrier, B, barrier).
 #include "helix_common.hpp"
 #include "kernels.hpp"
 
@@ -313,7 +313,11 @@ __device__ __forceinline__ void pair_sweep(const __bf16* __restrict__ q, const _
   const int nb = (S - m_start + RB - 1) / RB;                // blocks to sweep
   const int nfull = (S - m_start) / RB;                      // of which complete
   // pipelined blocks [i0, i1): after the blocks the causal diagonal cuts, starting at stage 0, 1 + 7 g of them
-  const int i0 = CAUSAL ? NST : 0;
+  const int i0 = CAUSAL ? G::BN / RB : 0;
+  // Block i lives in stage (i + kStageShift) % NSTAGE: the first pipelined block sits in stage 0, where the
+  // unrolled loop starts, without padding the plain prefix to a multiple of seven.
+  constexpr int kStageShift = CAUSAL ? NST - G::BN / RB : 0;
+  auto stage_of = [&](int i) __attribute__((always_inline)) { return (i + kStageShift) % NST; };
   int i1 = i0;
   // (every copy they issue, up to block i1 - 1 + AHEAD, and the 64 statistics rows it reads are whole)
   const int navail = nfull - (G::AHEAD + 1) - i0;
@@ -331,18 +335,18 @@ __device__ __forceinline__ void pair_sweep(const __bf16* __restrict__ q, const _
   };
   // Runtime-stage copy of block i + AHEAD at the start of iteration i (stage = (i + AHEAD) % 7).
   auto copy_ahead = [&](int i) __attribute__((always_inline)) {
-    if (i + G::AHEAD < nb) copy_block(i + G::AHEAD, (i + G::AHEAD) % NST);
+    if (i + G::AHEAD < nb) copy_block(i + G::AHEAD, stage_of(i + G::AHEAD));
   };
 #pragma unroll
   for (int i = 0; i < G::AHEAD; i++)
-    if (i < nb) copy_block(i, i);
+    if (i < nb) copy_block(i, stage_of(i));
   wait_tile_loads();
   __syncthreads();
 
   // ---- plain path: block i in program order (A, barrier, B, barrier), masks applied by A
   auto plain_block = [&](int i) __attribute__((always_inline)) {
-    const int so = (i % NST) * G::BLOCK;                         // stage offset inside a ring
-    const uint32_t stat = ln.astat + (i % NST) * G::STAT_STAGE;
+    const int so = stage_of(i) * G::BLOCK;                       // stage offset inside a ring
+    const uint32_t stat = ln.astat + stage_of(i) * G::STAT_STAGE;
     const int r0 = m_start + i * RB;
     copy_ahead(i);
     if constexpr (role == 0) {
@@ -477,7 +481,7 @@ __device__ __forceinline__ void pair_sweep(const __bf16* __restrict__ q, const _
     }
     // ---- drain: B finishes block i1 - 1 (its dP is in xb, its P in the buffer A wrote last)
     if constexpr (role == 1) {
-      const int so = ((i1 - 1) % NST) * G::BLOCK;
+      const int so = stage_of(i1 - 1) * G::BLOCK;
       f32x16 ds;
 #pragma unroll
       for (int g = 0; g < 4; g++) {
