@@ -1,26 +1,29 @@
 // dK / dV pass of the attention backward, head dimension 128, TWO waves per SIMD (Table 1,
-// Attention column, "Backward B").  Same arithmetic, in the same order, as bwd_dkdv.hip: the
-// results are bit-identical; what differs is the division of labour.
+// Attention column, "Backward B").  The arithmetic is that of bwd_dkdv.hip (dV comes out bit
+// for bit the same; dK differs in the last bit of some elements because here -delta is the
+// initial accumulator of the dP product in every code path); what differs is the division of
+// labour.
 //
 // The one-wave-per-SIMD kernel keeps S, dP, dK^T and dV^T of 32 keys in one wave (364
-// registers) and is bound by instruction issue: a single wave issues about one instruction
-// per four cycles whatever it is, and there are eight of them per MFMA.  Here a workgroup of
-// 8 waves owns the same 128 keys, but each group of 32 keys belongs to a PAIR of waves:
+// registers at this head dimension) and is bound by instruction issue: a single wave issues
+// about one instruction per four cycles whatever it is, and there are eight of them per MFMA.
+// Here a workgroup of 8 waves owns the same 128 keys, but each group of 32 keys belongs to a
+// PAIR of waves:
 //     wave A (waves 0..3):  S = Q K^T,  P = exp2(S*c - lse2),  dV^T += dO^T bf16(P)
 //     wave B (waves 4..7):  dP = dO V^T - delta,  dS = P o dP,  dK^T += Q^T bf16(dS)
 // A hands P (fp32, register for register: both accumulators have the same lane layout)
 // to B through LDS; B works one 32-row block behind A, and one workgroup barrier per block
-// orders the hand-over.  Each wave needs about 200 registers, so two fit on a SIMD and the
+// orders the hand-over.  Each wave needs 216-233 registers, so two fit on a SIMD and the
 // instructions of one issue under the MFMAs of the other; per MFMA a wave issues about two
 // vector-ALU and two LDS instructions.
 //
-// Tiles.  Q / dO are staged per 32-row block in SEVEN 16 KB stages (block i-1 is read by B,
-// i and i+1 by both, i+2 is prefetched, i+3 and i+4 are landing, i+5 is being issued) plus
-// small rings for lse2 / -delta.  The block loop is unrolled seven times, so the stage of
-// every LDS access is a compile-time immediate added to one of two anchor registers (the
-// offset field of an LDS instruction reaches 64 KB): the loop contains no address arithmetic
-// at all.  Blocks cut by the causal diagonal and whatever remains at the end run through a
-// plain path (A, barrier, B, barrier).
+// Tiles.  Q and dO are staged per 32-row block (8 KB each) in two rings of SEVEN stages (block
+// i-1 is read by B, i and i+1 by both, i+2 is prefetched, i+3 and i+4 are landing, i+5 is being
+// issued) plus small rings for lse2 / -delta.  The block loop is unrolled seven times, so the
+// stage of every LDS access is a compile-time immediate added to the lane's address register
+// (a whole ring is within the 64 KB reach of an LDS instruction's offset field): the loop
+// contains no address arithmetic at all.  Blocks cut by the causal diagonal and whatever
+// remains at the end run through a plain path (A, barrier, B, barrier).
 #include "helix_common.hpp"
 #include "kernels.hpp"
 
