@@ -38,3 +38,9 @@ def test_full_attention_block_regimes(S):
 @pytest.mark.parametrize("S", CAUSAL)
 def test_causal_block_regimes(S):
     _check(S, True, 7200 + S)
+
+
+def test_full_attention_many_groups_and_ragged_end():
+    """Full attention at a length with 36 seven-block groups per key tile and a ragged last block: every key tile
+    runs the pipelined path from its first block (there is no diagonal) for hundreds of blocks."""
+    _check(32 * 259 + 17, False, 7300)
